@@ -1,0 +1,150 @@
+"""Benchmark of the FLASH-D attention forward path on one MI355X.
+
+A step is one flashd_attn_fwd call (the whole hot path: Q load, K/V streaming, scores,
+mask, weight recurrence, blend, store) on the LLaMA-7B-like causal bf16 prefill workload;
+the inputs are resident in HBM before the timed region and rotate over several independent
+sets so that the last-level cache is not flattering.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode]
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 matrix peak
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
+
+
+def time_calls(fn, steps, warmup, nsets):
+    """Wall time and HIP-event time (on the launch stream) of `steps` calls of fn(i % nsets)."""
+    for i in range(warmup):
+        fn(i % nsets)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        fn(i % nsets)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms, ev0.elapsed_time(ev1)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--sets", type=int, default=4, help="independent input sets to rotate over")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
+    ap.add_argument("--no-ablation", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU; this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+
+    from paper_2505_14201_amd import flashd, synthetic
+
+    w = synthetic.CONFIGS[1]
+    q, k, v, _ = synthetic.make_qkv(w)
+    sets = []
+    for s in range(args.sets):
+        if s == 0:
+            qs, ks, vs = q, k, v
+        else:   # further sets: same distribution, different seed
+            qs, ks, vs, _ = synthetic.make_qkv(dataclasses.replace(w, seed=w.seed + 100 * s))
+        qg, kg, vg = qs.cuda(), ks.cuda(), vs.cuda()
+        sets.append((qg, kg, vg, torch.empty_like(qg)))
+    torch.cuda.synchronize()
+
+    def step(i):
+        qg, kg, vg, og = sets[i]
+        flashd.attn_fwd(qg, kg, vg, og, w.causal, w.scale)
+
+    wall_ms, ev_ms = time_calls(step, args.steps, args.warmup, args.sets)
+    ms_per_step = wall_ms / args.steps
+    kern_ms = ev_ms / args.steps
+    flops = w.flops()
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "attention fwd TFLOP/s (causal bf16 prefill, FLASH-D form)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "Lq": w.Lq,
+                   "Lk": w.Lk, "d": w.d, "causal": w.causal, "input_sets": args.sets,
+                   "flop_per_step": flops},
+        "roofline": {"bound": "mfma", "kernel": "tile_kernel<BF16,128> (flashd_attn_fwd)",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel_ms": round(kern_ms, 4)},
+    }
+
+    # parity of what was just timed, against the oracle, and the oracle's own speed
+    if not args.no_cpu:
+        from oracle import attention as oa
+        t0 = time.perf_counter()
+        ref = oa.attn(q, k, v, w.causal, w.scale)
+        cpu_s = time.perf_counter() - t0
+        got = sets[0][3].cpu().double().numpy()
+        err = np.abs(got - ref)
+        out["parity"] = {"max_abs_err": float(err.max()),
+                         "rel_rms_err": float(np.sqrt((err ** 2).sum() / (ref ** 2).sum())),
+                         "rows_checked": int(w.B * w.Hq * w.Lq)}
+        out["cpu_baseline"] = {"value": round(flops / cpu_s / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oa.num_threads(), "kind": "oracle",
+                               "sample": "the whole workload (all B*Hq*Lq rows), fp64 definition",
+                               "seconds": round(cpu_s, 2)}
+        del ref, got, err
+
+    if not args.no_ablation:
+        def step_abl(i):
+            qg, kg, vg, og = sets[i]
+            flashd.attn_fwd_ex(qg, kg, vg, og, w.causal, w.scale, flashd.VARIANT_ONLINE_SOFTMAX, 1)
+        _, ev_abl = time_calls(step_abl, args.steps, args.warmup, args.sets)
+        out["ablation_online_softmax"] = {
+            "kernel_ms": round(ev_abl / args.steps, 4),
+            "TFLOP/s": round(flops / (ev_abl / args.steps * 1e-3) / 1e12, 2)}
+
+    del sets
+    torch.cuda.empty_cache()
+
+    if not args.no_decode:
+        wd = synthetic.CONFIGS[3]
+        qd, kd, vd, _ = synthetic.make_qkv(wd)
+        qg, kg, vg = qd.cuda(), kd.cuda(), vd.cuda()
+        og = torch.empty_like(qg)
+
+        def step_dec(_):
+            flashd.attn_fwd(qg, kg, vg, og, wd.causal, wd.scale)
+        dsteps = max(10, args.steps // 2)
+        _, ev_dec = time_calls(step_dec, dsteps, 5, 1)
+        dms = ev_dec / dsteps
+        gbs = wd.bytes_io() / (dms * 1e-3) / 1e9
+        out["decode"] = {"workload": wd.name, "ms_per_step": round(dms, 4),
+                         "bytes_per_step": wd.bytes_io(),
+                         "roofline": {"bound": "hbm", "achieved": round(gbs, 1),
+                                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                      "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

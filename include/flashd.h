@@ -1,0 +1,115 @@
+/*
+ * libflashd -- the FlashAttention forward pass in the FLASH-D form, for AMD MI355X (gfx950).
+ *
+ * What is computed (Sec. II-A, problem statement): for every batch b, query head h and
+ * query row i,
+ *
+ *     s_j = scale * dot(q[b,h,i,:], k[b,kvh,j,:])          kvh = h / (Hq / Hkv)
+ *     o[b,h,i,:] = sum_j softmax_j(s)_j * v[b,kvh,j,:]      over the keys j visible to i
+ *
+ * How it is computed (Sec. III, Alg. 3): the output is built key by key as the blend
+ * o_i = o_{i-1} + (v_i - o_{i-1}) w_i with w_1 = 1 and
+ * w_i = sigmoid(s_i - s_{i-1} + ln w_{i-1}); there is no running maximum, no running sum of
+ * exponentials and no division of the output.  Runs of keys (tiles, split-K partitions) are
+ * folded by the same rule, a run acting as one key whose score is s_last - ln w_last.
+ *
+ * Conventions shared by every entry point
+ *   - q, k, v, o and workspace are DEVICE pointers owned by the caller; the library never
+ *     frees or keeps them beyond the work it enqueues.  They must be 16-byte aligned.
+ *   - Layout, row-major and contiguous: q, o: [B][Hq][Lq][d];  k, v: [B][Hkv][Lk][d];
+ *     all four in the storage type named by `dtype`.  o must not overlap an input.
+ *   - B, Hq, Hkv, Lq, Lk >= 1; Hq % Hkv == 0; d is 64 or 128.
+ *   - causal != 0: key j is visible to query i iff j <= i + (Lk - Lq) (the last query sees
+ *     every key).  A query row with no visible key yields zeros.  causal == 0: all keys.
+ *   - `scale` multiplies the dot product in fp32.  State and accumulation are fp32 for all
+ *     storage types.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; they do not synchronise.
+ *   - Every function returns a flashd_status (0 = success, negative = error).  On an error
+ *     nothing has been enqueued.  Argument errors are detected before any GPU call.
+ *   - For fixed inputs, variant and splits the output is bitwise reproducible.
+ */
+#ifndef FLASHD_H
+#define FLASHD_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FLASHD_F32 = 0, FLASHD_F16 = 1, FLASHD_BF16 = 2 } flashd_dtype;
+
+typedef enum {
+    FLASHD_OK = 0,
+    FLASHD_E_NULL = -1,       /* q, k, v or o is NULL                                   */
+    FLASHD_E_SHAPE = -2,      /* a dimension is < 1, or a size overflows                */
+    FLASHD_E_DTYPE = -3,      /* dtype is not a flashd_dtype                            */
+    FLASHD_E_HEADDIM = -4,    /* d is not 64 or 128                                     */
+    FLASHD_E_GQA = -5,        /* Hq is not a multiple of Hkv                            */
+    FLASHD_E_ALIGN = -6,      /* a pointer is not 16-byte aligned                       */
+    FLASHD_E_WORKSPACE = -7,  /* workspace missing or smaller than flashd_workspace_bytes */
+    FLASHD_E_HIP = -8,        /* a HIP call (allocation, launch) failed                 */
+    FLASHD_E_ARCH = -9,       /* the current device is not gfx950                       */
+    FLASHD_E_VARIANT = -10    /* variant/splits not valid for this problem              */
+} flashd_status;
+
+/* How the recurrence is evaluated.  All variants compute the same result. */
+typedef enum {
+    FLASHD_VARIANT_AUTO = 0,     /* TILE for f16/bf16, PER_KEY for f32                      */
+    FLASHD_VARIANT_TILE = 1,     /* Alg. 3 lifted to key tiles on the matrix cores (f16/bf16) */
+    FLASHD_VARIANT_PER_KEY = 2,  /* Alg. 3 literally, one sigmoid per key (any dtype)       */
+    FLASHD_VARIANT_ONLINE_SOFTMAX = 3  /* ablation: Alg. 2 (running max, sum, final division)
+                                          on the same tiling as TILE (f16/bf16)             */
+} flashd_variant;
+
+/*
+ * Attention forward, Alg. 3 (Sec. III-C).  Picks the variant and the number of key splits
+ * itself and takes split-K scratch memory from a grow-only cache kept per (device, stream);
+ * the first call that needs a larger cache allocates (hipMalloc), later calls do not.
+ * Safe to call from several host threads; calls that share a stream share its cache and are
+ * ordered by the stream.
+ */
+int flashd_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                    int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                    int causal, float scale, int dtype, void* stream);
+
+/*
+ * Same computation with explicit knobs.
+ *   variant   a flashd_variant; TILE and ONLINE_SOFTMAX need f16/bf16 (else FLASHD_E_VARIANT).
+ *   splits    number of consecutive key ranges reduced independently and then merged with
+ *             the sigmoid rule; 0 = choose, 1 = no split; at most FLASHD_MAX_SPLITS and at
+ *             most Lk (else FLASHD_E_VARIANT).
+ *   workspace device memory of at least flashd_workspace_bytes(..., splits) bytes, used only
+ *             while the enqueued work runs; may be NULL when that size is 0.  With
+ *             splits == 0 pass the size for splits = 0, which covers whatever is chosen.
+ * Never allocates.
+ */
+int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
+                       int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                       int causal, float scale, int dtype, void* stream,
+                       int variant, int splits, void* workspace, size_t workspace_bytes);
+
+#define FLASHD_MAX_SPLITS 64
+
+/*
+ * Bytes of workspace flashd_attn_fwd_ex needs: one partial state (o[d], s, ln w) in fp32 per
+ * (split, b, h, i) when more than one split is used (the state of Alg. 3, Sec. III-C), else 0.
+ * splits == 0 returns the bound for the automatic choice.  Returns 0 for invalid arguments.
+ */
+size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
+                              int variant, int splits);
+
+/* The number of splits the automatic choice takes for this problem (>= 1). */
+int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant);
+
+/* Static, NUL-terminated description of a status code. */
+const char* flashd_status_string(int status);
+
+/* major * 10000 + minor * 100 + patch */
+int flashd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHD_H */

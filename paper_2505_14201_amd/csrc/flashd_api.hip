@@ -1,0 +1,213 @@
+// The C ABI of libflashd: argument validation, variant/split selection, the
+// per-(device, stream) workspace cache, and dispatch to the kernel launchers.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "../../include/flashd.h"
+#include "flashd_common.h"
+#include "flashd_kernels.h"
+
+namespace {
+
+using flashd::Problem;
+
+struct Shape { int B, Hq, Hkv, Lq, Lk, d, dtype; };
+
+int validate_shape(const Shape& s) {
+    if (s.B < 1 || s.Hq < 1 || s.Hkv < 1 || s.Lq < 1 || s.Lk < 1) return FLASHD_E_SHAPE;
+    if (s.B > 65535 || s.Hq > 65535) return FLASHD_E_SHAPE;          // grid y/z limits
+    if (s.dtype != FLASHD_F32 && s.dtype != FLASHD_F16 && s.dtype != FLASHD_BF16)
+        return FLASHD_E_DTYPE;
+    if (s.d != 64 && s.d != 128) return FLASHD_E_HEADDIM;
+    if (s.Hq % s.Hkv != 0) return FLASHD_E_GQA;
+    // element counts must fit 2^40 so every byte offset fits size_t with room to spare
+    const long double nq = (long double)s.B * s.Hq * s.Lq * s.d;
+    const long double nk = (long double)s.B * s.Hkv * s.Lk * s.d;
+    if (nq > 1.0e12L || nk > 1.0e12L) return FLASHD_E_SHAPE;
+    return FLASHD_OK;
+}
+
+int resolve_variant(const Shape& s, int variant) {
+    if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_ONLINE_SOFTMAX) return -1;
+    if (variant == FLASHD_VARIANT_AUTO)
+        return s.dtype == FLASHD_F32 ? FLASHD_VARIANT_PER_KEY : FLASHD_VARIANT_TILE;
+    if (s.dtype == FLASHD_F32 && variant != FLASHD_VARIANT_PER_KEY) return -1;
+    return variant;
+}
+
+int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
+
+// Splits for the automatic choice: enough independent work to fill 256 compute units
+// several times over, but never key ranges shorter than 256 keys.
+int auto_splits(const Shape& s, int variant) {
+    long units;
+    if (variant == FLASHD_VARIANT_PER_KEY) {
+        const int rows_per_group = (s.d <= 64 ? 2 : 1) * 4;             // 4 wavefronts
+        units = (long)s.B * s.Hq * ceil_div(s.Lq, rows_per_group);      // workgroups
+    } else {
+        units = flashd::tile_workgroups(s.B, s.Hq, s.Hkv, s.Lq, s.d);
+    }
+    const long target = 1024;
+    if (units < 1) units = 1;
+    long sp = units >= target ? 1 : ceil_div(target, units);
+    const long by_len = s.Lk / 256 > 0 ? s.Lk / 256 : 1;
+    if (sp > by_len) sp = by_len;
+    if (sp > FLASHD_MAX_SPLITS) sp = FLASHD_MAX_SPLITS;
+    if (sp < 1) sp = 1;
+    return (int)sp;
+}
+
+size_t ws_bytes(const Shape& s, int splits) {
+    if (splits <= 1) return 0;
+    return (size_t)splits * s.B * s.Hq * s.Lq * (size_t)(s.d + 2) * sizeof(float);
+}
+
+// ---- device check ----------------------------------------------------------
+
+std::mutex g_mu;
+std::map<int, int> g_arch_ok;      // device -> 1 ok / 0 not gfx950
+
+int check_arch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_arch_ok.find(dev);
+    if (it == g_arch_ok.end()) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return FLASHD_E_HIP;
+        }
+        const int ok = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
+        it = g_arch_ok.emplace(dev, ok).first;
+    }
+    return it->second ? FLASHD_OK : FLASHD_E_ARCH;
+}
+
+// ---- workspace cache: grow-only, one buffer per (device, stream) -----------
+// A buffer that is outgrown is kept until the process ends, because work
+// enqueued earlier on the stream may still be reading it.
+
+struct CacheEntry { void* ptr = nullptr; size_t bytes = 0; };
+std::map<std::pair<int, void*>, CacheEntry> g_cache;
+
+int cached_workspace(void* stream, size_t bytes, void** out) {
+    *out = nullptr;
+    if (bytes == 0) return FLASHD_OK;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+    std::lock_guard<std::mutex> lk(g_mu);
+    CacheEntry& e = g_cache[std::make_pair(dev, stream)];
+    if (e.bytes < bytes) {
+        size_t want = e.bytes * 2 > bytes ? e.bytes * 2 : bytes;
+        void* p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+        e.ptr = p;
+        e.bytes = want;
+    }
+    *out = e.ptr;
+    return FLASHD_OK;
+}
+
+// ---- common front end --------------------------------------------------------
+
+int run(const void* q, const void* k, const void* v, void* o, const Shape& s, int causal,
+        float scale, void* stream, int variant, int splits, void* workspace,
+        size_t workspace_bytes, bool use_cache) {
+    if (!q || !k || !v || !o) return FLASHD_E_NULL;
+    int rc = validate_shape(s);
+    if (rc != FLASHD_OK) return rc;
+    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o |
+                           (uintptr_t)workspace;
+    if (bits & 15u) return FLASHD_E_ALIGN;
+    const int var = resolve_variant(s, variant);
+    if (var < 0) return FLASHD_E_VARIANT;
+    if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
+    const int sp = splits == 0 ? auto_splits(s, var) : splits;
+    const size_t need = ws_bytes(s, sp);
+    if (!use_cache && need > 0 && (workspace == nullptr || workspace_bytes < need))
+        return FLASHD_E_WORKSPACE;
+
+    rc = check_arch();
+    if (rc != FLASHD_OK) return rc;
+    void* ws = workspace;
+    if (use_cache) {
+        rc = cached_workspace(stream, need, &ws);
+        if (rc != FLASHD_OK) return rc;
+    }
+
+    Problem p;
+    p.q = q; p.k = k; p.v = v; p.o = o;
+    p.ws = static_cast<float*>(ws);
+    p.B = s.B; p.Hq = s.Hq; p.Hkv = s.Hkv; p.Lq = s.Lq; p.Lk = s.Lk; p.d = s.d;
+    p.dtype = s.dtype;
+    p.causal = causal != 0;
+    p.splits = sp;
+    p.scale = scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (var == FLASHD_VARIANT_PER_KEY) e = flashd::launch_perkey(p, st);
+    else e = flashd::launch_tile(p, var == FLASHD_VARIANT_ONLINE_SOFTMAX, st);
+    return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flashd_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv,
+                    int Lq, int Lk, int d, int causal, float scale, int dtype, void* stream) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true);
+}
+
+int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B, int Hq,
+                       int Hkv, int Lq, int Lk, int d, int causal, float scale, int dtype,
+                       void* stream, int variant, int splits, void* workspace,
+                       size_t workspace_bytes) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    return run(q, k, v, o, s, causal, scale, stream, variant, splits, workspace, workspace_bytes,
+               false);
+}
+
+int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    if (validate_shape(s) != FLASHD_OK) return 1;
+    const int var = resolve_variant(s, variant);
+    if (var < 0) return 1;
+    return auto_splits(s, var);
+}
+
+size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
+                              int variant, int splits) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    if (validate_shape(s) != FLASHD_OK) return 0;
+    const int var = resolve_variant(s, variant);
+    if (var < 0 || splits < 0 || splits > FLASHD_MAX_SPLITS || splits > Lk) return 0;
+    return ws_bytes(s, splits == 0 ? auto_splits(s, var) : splits);
+}
+
+const char* flashd_status_string(int status) {
+    switch (status) {
+    case FLASHD_OK: return "ok";
+    case FLASHD_E_NULL: return "q, k, v or o is NULL";
+    case FLASHD_E_SHAPE: return "a dimension is out of range";
+    case FLASHD_E_DTYPE: return "unknown dtype";
+    case FLASHD_E_HEADDIM: return "head dimension must be 64 or 128";
+    case FLASHD_E_GQA: return "Hq must be a multiple of Hkv";
+    case FLASHD_E_ALIGN: return "pointers must be 16-byte aligned";
+    case FLASHD_E_WORKSPACE: return "workspace missing or too small";
+    case FLASHD_E_HIP: return "a HIP call failed";
+    case FLASHD_E_ARCH: return "the current device is not gfx950";
+    case FLASHD_E_VARIANT: return "variant or splits not valid for this problem";
+    default: return "unknown status";
+    }
+}
+
+int flashd_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,121 @@
+// Shared device-side pieces of libflashd: storage-type traits, the problem
+// descriptor passed to kernels, and the sigmoid-rule primitives on a state.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace flashd {
+
+constexpr int kWave = 64;
+
+struct Problem {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    float* ws;          // split-K partial states, [splits][B][Hq][Lq][d + 2] fp32
+    int B, Hq, Hkv, Lq, Lk, d;
+    int dtype;          // flashd_dtype: 0 f32, 1 f16, 2 bf16
+    int causal;         // 0/1
+    int splits;         // >= 1
+    float scale;
+};
+
+// ---- storage types -------------------------------------------------------
+
+struct F32 { using raw = float; };
+struct F16 { using raw = _Float16; };
+struct BF16 { using raw = uint16_t; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t x) {
+    return __uint_as_float(static_cast<uint32_t>(x) << 16);
+}
+
+// round-to-nearest-even; inputs here are finite or +-inf (NaN stays NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+template <typename T> struct Store;
+template <> struct Store<F32> {
+    static __device__ __forceinline__ float load(const void* p, size_t i) {
+        return static_cast<const float*>(p)[i];
+    }
+    static __device__ __forceinline__ void store(void* p, size_t i, float x) {
+        static_cast<float*>(p)[i] = x;
+    }
+    // 8 consecutive elements starting at element index i (i % 8 == 0)
+    static __device__ __forceinline__ void load8(const void* p, size_t i, float (&out)[8]) {
+        const float4* s = reinterpret_cast<const float4*>(static_cast<const float*>(p) + i);
+        float4 a = s[0], b = s[1];
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    }
+};
+template <> struct Store<F16> {
+    static __device__ __forceinline__ float load(const void* p, size_t i) {
+        return static_cast<float>(static_cast<const _Float16*>(p)[i]);
+    }
+    static __device__ __forceinline__ void store(void* p, size_t i, float x) {
+        static_cast<_Float16*>(p)[i] = static_cast<_Float16>(x);
+    }
+    static __device__ __forceinline__ void load8(const void* p, size_t i, float (&out)[8]) {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        h8 a = *reinterpret_cast<const h8*>(static_cast<const _Float16*>(p) + i);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t] = static_cast<float>(a[t]);
+    }
+};
+template <> struct Store<BF16> {
+    static __device__ __forceinline__ float load(const void* p, size_t i) {
+        return bf16_to_f32(static_cast<const uint16_t*>(p)[i]);
+    }
+    static __device__ __forceinline__ void store(void* p, size_t i, float x) {
+        static_cast<uint16_t*>(p)[i] = f32_to_bf16(x);
+    }
+    static __device__ __forceinline__ void load8(const void* p, size_t i, float (&out)[8]) {
+        uint4 a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + i);
+        uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            out[2 * t] = __uint_as_float(w[t] << 16);
+            out[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+        }
+    }
+};
+
+// ---- the sigmoid rule ------------------------------------------------------
+//
+// Weight equation of Sec. III-B: w_i = sigmoid(x), x = s_i - s_{i-1} + ln w_{i-1}.
+// The next step needs ln w_i; it is taken from x (ln sigmoid(x)), never from the
+// rounded w_i, so a weight that rounds to 0 or 1 still carries its logarithm.
+// Both are evaluated through e^{-|x|} <= 1, which cannot overflow: this is the
+// saturation the paper's stability argument (Sec. III-C) relies on.
+__device__ __forceinline__ void sigmoid_and_log(float x, float& w, float& lnw) {
+    float e = __expf(-fabsf(x));          // in (0, 1]; 0 once |x| > ~104
+    float t = 1.0f + e;
+    float r = __frcp_rn(t);
+    float lt = __logf(t);                 // ln(1 + e) in [0, ln 2]
+    bool pos = x >= 0.0f;
+    w = pos ? r : e * r;
+    lnw = pos ? -lt : x - lt;
+}
+
+// A run of keys is summarised by (o, lam) with lam = s_last - ln w_last; the empty
+// run has lam = -inf.  Appending run B to run A treats B as one key of score lam_b
+// and value o_b: W = sigmoid(lam_b - lam_a), o = o_a + (o_b - o_a) W (Sec. IV-A
+// form of the blend), lam = lam_b - ln W.
+__device__ __forceinline__ void merge_weight(float lam_a, float lam_b, float& W, float& lam) {
+    const float ninf = -__builtin_inff();
+    if (lam_b == ninf) { W = 0.0f; lam = lam_a; return; }
+    if (lam_a == ninf) { W = 1.0f; lam = lam_b; return; }
+    float lnW;
+    sigmoid_and_log(lam_b - lam_a, W, lnW);
+    lam = lam_b - lnW;
+}
+
+}  // namespace flashd

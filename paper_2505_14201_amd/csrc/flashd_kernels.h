@@ -1,0 +1,24 @@
+// Host-side launchers of the kernel files, called by the C-ABI layer.  Each
+// checks nothing: the ABI layer has validated the problem before it gets here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "flashd_common.h"
+
+namespace flashd {
+
+// Alg. 3 per key (any dtype); with p.splits > 1 also folds the partials.
+hipError_t launch_perkey(const Problem& p, hipStream_t st);
+
+// Fold p.splits partial states per query row from p.ws into p.o.
+hipError_t launch_merge_splits(const Problem& p, hipStream_t st);
+
+// Alg. 3 on key tiles (matrix cores, f16/bf16); online = the Alg. 2 ablation.
+// With p.splits > 1 also folds the partials.
+hipError_t launch_tile(const Problem& p, bool online, hipStream_t st);
+
+// Number of workgroups launch_tile uses per split.
+long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d);
+
+}  // namespace flashd

@@ -1,0 +1,221 @@
+// Alg. 3 taken literally: one sigmoid per key (variant PER_KEY), any storage type,
+// fp32 arithmetic on the vector ALU.  This is the exact-by-construction path (fp32
+// inputs use it) and the slow reference for the tiled kernels.
+//
+// Work split: a wavefront owns R query rows of one (b, h) and one key range
+// (split).  Lane t walks keys k0+t, k0+t+64, ... and runs the recurrence of Alg. 3
+// over ITS subsequence with the state (s_prev, ln w_prev, o) in registers, exactly
+// as the algorithm box states it.  The 64 lane states are then folded pairwise by
+// the same sigmoid rule (a run of keys acts as one key with score
+// s_last - ln w_last), and so are the split partials in a second kernel.
+#include "flashd_common.h"
+#include "flashd_kernels.h"
+
+namespace flashd {
+
+template <int D> struct PerKeyCfg { static constexpr int R = (D <= 64) ? 2 : 1; };
+constexpr int kPerKeyWaves = 4;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kPerKeyWaves * kWave)
+void perkey_kernel(Problem p) {
+    constexpr int R = PerKeyCfg<D>::R;
+    constexpr int ROWS_PER_BLOCK = R * kPerKeyWaves;
+    __shared__ float lds[ROWS_PER_BLOCK][D];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int row_blocks = (p.Lq + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    const int rb = blockIdx.x % row_blocks;
+    const int sp = blockIdx.x / row_blocks;
+    const int h = blockIdx.y;
+    const int b = blockIdx.z;
+    const int kvh = h / (p.Hq / p.Hkv);
+    const int i0 = rb * ROWS_PER_BLOCK + wave * R;
+    if (i0 >= p.Lq) return;           // no barrier below: waves are independent
+
+    const size_t qbase = ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
+    const size_t kbase = ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
+
+    // query rows -> LDS (wave-private rows), read back as broadcasts
+    float (*qs)[D] = &lds[wave * R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = i0 + r;
+        for (int t = lane; t < D; t += kWave)
+            qs[r][t] = (i < p.Lq) ? Store<T>::load(p.q, qbase + (size_t)i * D + t) : 0.0f;
+    }
+
+    // key range of this split, and how many keys each row may see
+    const int chunk = (p.Lk + p.splits - 1) / p.splits;
+    const int k0 = sp * chunk;
+    int k1 = min(p.Lk, k0 + chunk);
+    int nvis[R];
+    int kend = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = i0 + r;
+        int n = p.Lk;
+        if (p.causal) n = min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
+        if (i >= p.Lq) n = 0;
+        nvis[r] = min(n, k1);
+        kend = max(kend, nvis[r]);
+    }
+
+    float o[R][D];
+    float s_prev[R], lnw[R];
+    bool has[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        s_prev[r] = 0.0f; lnw[r] = 0.0f; has[r] = false;
+#pragma unroll
+        for (int t = 0; t < D; ++t) o[r][t] = 0.0f;
+    }
+
+    for (int j = k0 + lane; j < kend; j += kWave) {
+        const size_t krow = kbase + (size_t)j * D;
+        float s[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) s[r] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            float kk[8];
+            Store<T>::load8(p.k, krow + c * 8, kk);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int t = 0; t < 8; ++t) s[r] = fmaf(qs[r][c * 8 + t], kk[t], s[r]);
+        }
+        float w[R];
+        bool vis[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            vis[r] = j < nvis[r];
+            const float sj = p.scale * s[r];
+            float wi = 1.0f, lw = 0.0f;                 // first key: w_1 = 1
+            if (has[r]) sigmoid_and_log(sj - s_prev[r] + lnw[r], wi, lw);
+            if (vis[r]) { w[r] = wi; lnw[r] = lw; s_prev[r] = sj; has[r] = true; }
+            else w[r] = 0.0f;                           // a masked key is not an iteration
+        }
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            float vv[8];
+            Store<T>::load8(p.v, krow + c * 8, vv);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (vis[r]) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        float& acc = o[r][c * 8 + t];
+                        acc = fmaf(vv[t] - acc, w[r], acc);   // o + (v - o) w
+                    }
+                }
+        }
+    }
+
+    // fold the 64 lane states; the lower lane's keys come first
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float lam = has[r] ? s_prev[r] - lnw[r] : -__builtin_inff();
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const bool upper = (lane & off) != 0;
+            const float lam_x = __shfl_xor(lam, off, kWave);
+            const float lam_a = upper ? lam_x : lam;
+            const float lam_b = upper ? lam : lam_x;
+            float W, lam_n;
+            merge_weight(lam_a, lam_b, W, lam_n);
+#pragma unroll
+            for (int t = 0; t < D; ++t) {
+                const float ox = __shfl_xor(o[r][t], off, kWave);
+                const float oa = upper ? ox : o[r][t];
+                const float ob = upper ? o[r][t] : ox;
+                o[r][t] = fmaf(ob - oa, W, oa);
+            }
+            lam = lam_n;
+        }
+        const int i = i0 + r;
+        if (i >= p.Lq) continue;
+        if (lane == 0) {
+#pragma unroll
+            for (int t = 0; t < D; ++t) qs[r][t] = o[r][t];
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (p.splits == 1) {
+            const size_t obase = qbase + (size_t)i * D;
+            for (int t = lane; t < D; t += kWave) Store<T>::store(p.o, obase + t, qs[r][t]);
+        } else {
+            // partial state (o, s, ln w): the run acts as one key of score lam, weight 1
+            float* dst = p.ws + ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + i) * (D + 2);
+            for (int t = lane; t < D; t += kWave) dst[t] = qs[r][t];
+            if (lane == 0) { dst[D] = lam; dst[D + 1] = 0.0f; }
+        }
+    }
+}
+
+// Fold the split partials of each query row left to right with the sigmoid rule.
+template <typename T, int D>
+__global__ __launch_bounds__(256)
+void merge_splits_kernel(Problem p) {
+    constexpr int C = D / 4;                       // threads per row, 4 elements each
+    const size_t rows = (size_t)p.B * p.Hq * p.Lq;
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t row = gid / C;
+    const int c = (int)(gid % C);
+    if (row >= rows) return;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float lam = -__builtin_inff();
+    for (int sp = 0; sp < p.splits; ++sp) {
+        const float* src = p.ws + ((size_t)sp * rows + row) * (D + 2);
+        const float lam_b = src[D] - src[D + 1];   // s - ln w
+        float W, lam_n;
+        merge_weight(lam, lam_b, W, lam_n);
+        lam = lam_n;
+        if (W != 0.0f) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = fmaf(src[c * 4 + t] - acc[t], W, acc[t]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) Store<T>::store(p.o, row * D + c * 4 + t, acc[t]);
+}
+
+template <typename T, int D>
+static hipError_t launch_merge_t(const Problem& p, hipStream_t st) {
+    const size_t threads = (size_t)p.B * p.Hq * p.Lq * (D / 4);
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    hipLaunchKernelGGL((merge_splits_kernel<T, D>), dim3(blocks), dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_perkey_t(const Problem& p, hipStream_t st) {
+    constexpr int ROWS_PER_BLOCK = PerKeyCfg<D>::R * kPerKeyWaves;
+    const int row_blocks = (p.Lq + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    dim3 grid((unsigned)(row_blocks * p.splits), (unsigned)p.Hq, (unsigned)p.B);
+    hipLaunchKernelGGL((perkey_kernel<T, D>), grid, dim3(kPerKeyWaves * kWave), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits == 1) return e;
+    return launch_merge_t<T, D>(p, st);
+}
+
+#define FLASHD_DISPATCH(FN, ...)                                                     \
+    do {                                                                             \
+        if (p.dtype == 0 && p.d == 64) return FN<F32, 64>(__VA_ARGS__);              \
+        if (p.dtype == 0 && p.d == 128) return FN<F32, 128>(__VA_ARGS__);            \
+        if (p.dtype == 1 && p.d == 64) return FN<F16, 64>(__VA_ARGS__);              \
+        if (p.dtype == 1 && p.d == 128) return FN<F16, 128>(__VA_ARGS__);            \
+        if (p.dtype == 2 && p.d == 64) return FN<BF16, 64>(__VA_ARGS__);             \
+        if (p.dtype == 2 && p.d == 128) return FN<BF16, 128>(__VA_ARGS__);           \
+        return hipErrorInvalidValue;                                                 \
+    } while (0)
+
+hipError_t launch_merge_splits(const Problem& p, hipStream_t st) {
+    FLASHD_DISPATCH(launch_merge_t, p, st);
+}
+
+hipError_t launch_perkey(const Problem& p, hipStream_t st) {
+    FLASHD_DISPATCH(launch_perkey_t, p, st);
+}
+
+}  // namespace flashd

@@ -1,0 +1,130 @@
+"""Thin ctypes binding over libflashd.so: argument marshalling only.
+
+Function names mirror the C ABI in include/flashd.h.  Tensors are torch CUDA
+(ROCm) tensors used purely as owners of device memory; every step of the
+computation runs inside the library's HIP kernels.  There is no fallback: if the
+shared library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflashd.so")
+
+F32, F16, BF16 = 0, 1, 2
+VARIANT_AUTO, VARIANT_TILE, VARIANT_PER_KEY, VARIANT_ONLINE_SOFTMAX = 0, 1, 2, 3
+MAX_SPLITS = 64
+
+_DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+
+EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
+           "flashd_auto_splits", "flashd_status_string", "flashd_version")
+
+
+class FlashdError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libflashd status {status}: {status_string(status)}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2505_14201_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i, f, p, z = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    base = [p, p, p, p, i, i, i, i, i, i, i, f, i, p]
+    lib.flashd_attn_fwd.restype = i
+    lib.flashd_attn_fwd.argtypes = base
+    lib.flashd_attn_fwd_ex.restype = i
+    lib.flashd_attn_fwd_ex.argtypes = base + [i, i, p, z]
+    lib.flashd_workspace_bytes.restype = z
+    lib.flashd_workspace_bytes.argtypes = [i] * 9
+    lib.flashd_auto_splits.restype = i
+    lib.flashd_auto_splits.argtypes = [i] * 8
+    lib.flashd_status_string.restype = ctypes.c_char_p
+    lib.flashd_status_string.argtypes = [i]
+    lib.flashd_version.restype = i
+    lib.flashd_version.argtypes = []
+    return lib
+
+
+_lib = _load()
+
+
+def raw() -> ctypes.CDLL:
+    """The loaded C library (for tests that call the ABI with hand-made arguments)."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.flashd_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(_lib.flashd_version())
+
+
+def workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dtype, variant=VARIANT_AUTO, splits=0) -> int:
+    return int(_lib.flashd_workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dtype, variant, splits))
+
+
+def auto_splits(B, Hq, Hkv, Lq, Lk, d, dtype, variant=VARIANT_AUTO) -> int:
+    return int(_lib.flashd_auto_splits(B, Hq, Hkv, Lq, Lk, d, dtype, variant))
+
+
+def _marshal(q, k, v, o):
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if q.dtype not in _DTYPE or not (k.dtype == v.dtype == o.dtype == q.dtype):
+        raise ValueError("q, k, v, o must share one of float32/float16/bfloat16")
+    if q.dim() != 4 or k.dim() != 4 or v.shape != k.shape or o.shape != q.shape:
+        raise ValueError("expected q,o: [B,Hq,Lq,d] and k,v: [B,Hkv,Lk,d]")
+    B, Hq, Lq, d = q.shape
+    Bk, Hkv, Lk, dk = k.shape
+    if Bk != B or dk != d:
+        raise ValueError("batch or head dimension mismatch between q and k")
+    return B, Hq, Hkv, Lq, Lk, d, _DTYPE[q.dtype]
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def attn_fwd(q, k, v, o, causal: bool, scale: float, stream=None) -> None:
+    """flashd_attn_fwd: o <- attention(q, k, v), enqueued on `stream` (default: current)."""
+    B, Hq, Hkv, Lq, Lk, d, dt = _marshal(q, k, v, o)
+    with torch.cuda.device(q.device):
+        st = _stream_ptr(stream)
+        rc = _lib.flashd_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                  B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale), dt, st)
+    if rc != 0:
+        raise FlashdError(rc)
+
+
+def attn_fwd_ex(q, k, v, o, causal: bool, scale: float, variant: int = VARIANT_AUTO,
+                splits: int = 0, workspace=None, stream=None) -> None:
+    """flashd_attn_fwd_ex: explicit variant/splits and a caller-owned workspace tensor
+    (any dtype, contiguous, on the same device) of at least workspace_bytes(...) bytes."""
+    B, Hq, Hkv, Lq, Lk, d, dt = _marshal(q, k, v, o)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous GPU tensor")
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    with torch.cuda.device(q.device):
+        st = _stream_ptr(stream)
+        rc = _lib.flashd_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                     B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale), dt,
+                                     st, int(variant), int(splits), ws_ptr, ws_bytes)
+    if rc != 0:
+        raise FlashdError(rc)

@@ -1,0 +1,133 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, and
+turns every invalid argument into its status code before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+from paper_2505_14201_amd import flashd  # noqa: E402
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_HEADDIM, E_GQA, E_ALIGN, E_WS, E_HIP, E_ARCH, E_VARIANT = \
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10
+
+P = 0x1000          # a non-null, 16-byte aligned fake pointer; never dereferenced on these paths
+
+
+def fwd(q=P, k=P, v=P, o=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=8, d=64, causal=0, scale=0.125,
+        dtype=flashd.BF16):
+    return flashd.raw().flashd_attn_fwd(q, k, v, o, B, Hq, Hkv, Lq, Lk, d, causal, scale, dtype,
+                                        None)
+
+
+def fwd_ex(variant=0, splits=0, ws=None, ws_bytes=0, **kw):
+    a = dict(q=P, k=P, v=P, o=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=512, d=64, causal=0, scale=0.125,
+             dtype=flashd.BF16)
+    a.update(kw)
+    return flashd.raw().flashd_attn_fwd_ex(a["q"], a["k"], a["v"], a["o"], a["B"], a["Hq"],
+                                           a["Hkv"], a["Lq"], a["Lk"], a["d"], a["causal"],
+                                           a["scale"], a["dtype"], None, variant, splits, ws,
+                                           ws_bytes)
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "flashd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(flashd_[a-z_]+)\s*\(", text))
+    assert declared == set(flashd.EXPORTS)
+    lib = ctypes.CDLL(flashd.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_header_constants_match_binding():
+    text = open(os.path.join(ROOT, "include", "flashd.h")).read()
+    enums = dict((k, int(v)) for k, v in re.findall(r"(FLASHD_[A-Z0-9_]+)\s*=\s*(-?\d+)", text))
+    assert (enums["FLASHD_F32"], enums["FLASHD_F16"], enums["FLASHD_BF16"]) == \
+        (flashd.F32, flashd.F16, flashd.BF16)
+    assert enums["FLASHD_VARIANT_TILE"] == flashd.VARIANT_TILE
+    assert enums["FLASHD_VARIANT_PER_KEY"] == flashd.VARIANT_PER_KEY
+    assert enums["FLASHD_VARIANT_ONLINE_SOFTMAX"] == flashd.VARIANT_ONLINE_SOFTMAX
+    assert int(re.search(r"#define FLASHD_MAX_SPLITS (\d+)", text).group(1)) == flashd.MAX_SPLITS
+    for name, val in enums.items():
+        if name.startswith("FLASHD_E_") or name == "FLASHD_OK":
+            s = flashd.status_string(val)
+            assert s and s != "unknown status"
+    assert flashd.status_string(-99) == "unknown status"
+    assert flashd.version() >= 100
+
+
+def test_null_pointers():
+    for name in ("q", "k", "v", "o"):
+        assert fwd(**{name: None}) == E_NULL
+
+
+def test_shape_errors():
+    for name in ("B", "Hq", "Hkv", "Lq", "Lk"):
+        assert fwd(**{name: 0}) == E_SHAPE
+        assert fwd(**{name: -3}) == E_SHAPE
+    assert fwd(B=70000) == E_SHAPE
+    assert fwd(B=60000, Hq=60000, Hkv=60000, Lq=100000, Lk=8) == E_SHAPE   # element count overflow
+
+
+def test_dtype_headdim_gqa_align():
+    assert fwd(dtype=3) == E_DTYPE
+    assert fwd(dtype=-1) == E_DTYPE
+    for d in (0, 32, 96, 256, 65):
+        assert fwd(d=d) == E_HEADDIM
+    assert fwd(Hq=5, Hkv=2) == E_GQA
+    for name in ("q", "k", "v", "o"):
+        assert fwd(**{name: P + 8}) == E_ALIGN
+    assert fwd_ex(ws=P + 4, ws_bytes=1 << 30, splits=2) == E_ALIGN
+
+
+def test_error_precedence_is_null_shape_dtype_headdim_gqa_align():
+    assert fwd(q=None, B=0, dtype=9, d=3, Hq=5) == E_NULL
+    assert fwd(B=0, dtype=9, d=3, Hq=5) == E_SHAPE
+    assert fwd(dtype=9, d=3, Hq=5) == E_DTYPE
+    assert fwd(d=3, Hq=5, q=P + 2) == E_HEADDIM
+    assert fwd(Hq=5, q=P + 2) == E_GQA
+
+
+def test_variant_and_split_errors():
+    assert fwd_ex(variant=4) == E_VARIANT
+    assert fwd_ex(variant=-1) == E_VARIANT
+    assert fwd_ex(variant=flashd.VARIANT_TILE, dtype=flashd.F32) == E_VARIANT
+    assert fwd_ex(variant=flashd.VARIANT_ONLINE_SOFTMAX, dtype=flashd.F32) == E_VARIANT
+    assert fwd_ex(splits=-1) == E_VARIANT
+    assert fwd_ex(splits=flashd.MAX_SPLITS + 1) == E_VARIANT
+    assert fwd_ex(splits=9, Lk=8) == E_VARIANT
+
+
+def test_workspace_errors_and_sizes():
+    need = flashd.workspace_bytes(1, 4, 2, 8, 512, 64, flashd.BF16, flashd.VARIANT_PER_KEY, 4)
+    assert need == 4 * 1 * 4 * 8 * (64 + 2) * 4
+    assert flashd.workspace_bytes(1, 4, 2, 8, 512, 64, flashd.BF16, flashd.VARIANT_PER_KEY, 1) == 0
+    assert fwd_ex(variant=flashd.VARIANT_PER_KEY, splits=4) == E_WS
+    assert fwd_ex(variant=flashd.VARIANT_PER_KEY, splits=4, ws=P, ws_bytes=need - 1) == E_WS
+    # invalid problems have no workspace size
+    assert flashd.workspace_bytes(1, 5, 2, 8, 512, 64, flashd.BF16, 0, 4) == 0
+    assert flashd.workspace_bytes(1, 4, 2, 8, 512, 48, flashd.BF16, 0, 4) == 0
+    # the automatic choice never exceeds the documented limits
+    for (B, Hq, Hkv, Lq, Lk, d, dt) in [(64, 32, 8, 1, 8192, 128, flashd.BF16),
+                                        (1, 1, 1, 128, 128, 64, flashd.F32),
+                                        (4, 32, 32, 2048, 2048, 128, flashd.BF16),
+                                        (1, 8, 8, 1, 100, 64, flashd.F16)]:
+        s = flashd.auto_splits(B, Hq, Hkv, Lq, Lk, d, dt)
+        assert 1 <= s <= min(flashd.MAX_SPLITS, Lk)
+        assert flashd.workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dt, 0, 0) == \
+            flashd.workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dt, 0, s)
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a machine without a GPU")
+def test_valid_arguments_without_a_gpu_report_hip_error():
+    assert fwd() == E_HIP
+
+
+def test_binding_rejects_cpu_tensors():
+    q = torch.zeros(1, 1, 4, 64)
+    with pytest.raises(ValueError):
+        flashd.attn_fwd(q, q, q, q, False, 1.0)

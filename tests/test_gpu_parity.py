@@ -1,0 +1,239 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs -- small shapes that span several tiles with ragged tails, every
+variant and split count, and the edge cases of the method."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2505_14201_amd import synthetic
+from tests.gpu_util import check, max_abs_score, run_flashd
+
+pytestmark = pytest.mark.gpu
+
+TILE, PER_KEY, ONLINE = 1, 2, 3
+DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def oracle(q, k, v, causal, scale, rows=None):
+    return oa.attn(q, k, v, causal, scale, "definition", rows)
+
+
+# (B, Hq, Hkv, Lq, Lk): several 128-row and 64-key tiles, ragged tails, Lq != Lk, GQA
+SHAPES = [
+    (1, 1, 1, 1, 1),
+    (1, 2, 1, 1, 300),
+    (2, 4, 2, 5, 70),
+    (1, 2, 2, 128, 128),
+    (1, 4, 1, 200, 333),
+    (1, 2, 2, 333, 200),      # causal: the first 133 rows see no key
+    (1, 1, 1, 257, 515),
+    (2, 8, 2, 64, 64),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE])
+def test_small_shapes_half(shape, causal, d, dtype, variant):
+    B, Hq, Hkv, Lq, Lk = shape
+    w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=1000 + Lq * 7 + Lk + d)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, w.scale)
+    got = run_flashd(q, k, v, causal, w.scale, variant, 1)
+    check(got, ref, DT[dtype], f"{shape} causal={causal} d={d} {dtype} variant={variant}")
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
+def test_small_shapes_f32(shape, causal, d):
+    B, Hq, Hkv, Lq, Lk = shape
+    w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, d, "f32", causal, seed=2000 + Lq * 7 + Lk + d)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, w.scale)
+    got = run_flashd(q, k, v, causal, w.scale, PER_KEY, 1)
+    check(got, ref, torch.float32, f"{shape} causal={causal} d={d} f32")
+    got = run_flashd(q, k, v, causal, w.scale, use_ex=False)
+    check(got, ref, torch.float32, f"{shape} causal={causal} d={d} f32 auto")
+
+
+@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE])
+@pytest.mark.parametrize("splits", [2, 3, 7, 0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_split_k_partials_merge_to_the_same_result(variant, splits, causal):
+    for (B, Hq, Hkv, Lq, Lk, d, dtype) in [(2, 4, 2, 1, 1000, 128, "bf16"),
+                                           (1, 2, 2, 150, 700, 64, "f16"),
+                                           (1, 8, 1, 3, 64, 128, "bf16")]:
+        w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=3000 + Lk + splits)
+        q, k, v, _ = synthetic.make_qkv(w)
+        ref = oracle(q, k, v, causal, w.scale)
+        got = run_flashd(q, k, v, causal, w.scale, variant, splits)
+        check(got, ref, DT[dtype], f"splits={splits} variant={variant} Lq={Lq} Lk={Lk}")
+
+
+def test_split_k_f32_and_more_splits_than_tiles():
+    w = synthetic.small("t", 1, 2, 1, 4, 130, 64, "f32", False, seed=3100)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, False, w.scale)
+    for splits in (2, 64):
+        check(run_flashd(q, k, v, False, w.scale, PER_KEY, splits), ref, torch.float32)
+    wb = synthetic.small("t", 1, 2, 1, 4, 130, 64, "bf16", True, seed=3101)
+    q, k, v, _ = synthetic.make_qkv(wb)
+    ref = oracle(q, k, v, True, wb.scale)
+    for variant in (TILE, ONLINE, PER_KEY):
+        check(run_flashd(q, k, v, True, wb.scale, variant, 64), ref, torch.bfloat16)
+
+
+def test_auto_entry_point_uses_cached_workspace_repeatedly():
+    """flashd_attn_fwd with split-K shapes of growing then shrinking size on one stream."""
+    for Lk in (600, 5000, 900):
+        w = synthetic.small("t", 2, 8, 2, 1, Lk, 128, "bf16", False, seed=3200 + Lk)
+        q, k, v, _ = synthetic.make_qkv(w)
+        ref = oracle(q, k, v, False, w.scale)
+        check(run_flashd(q, k, v, False, w.scale, use_ex=False), ref, torch.bfloat16, f"Lk={Lk}")
+
+
+# ------------------------------------------------------------ method invariants ---
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (TILE, "f16"), (PER_KEY, "f32"),
+                                           (PER_KEY, "bf16"), (ONLINE, "bf16")])
+def test_single_key_returns_its_value_bitwise(variant, dtype):
+    w = synthetic.small("t", 1, 2, 2, 70, 1, 64, dtype, False, seed=4000)
+    q, k, v, _ = synthetic.make_qkv(w)
+    got = run_flashd(q, k, v, False, w.scale, variant, 1)
+    want = v[:, :, 0:1, :].expand(-1, -1, 70, -1)
+    assert torch.equal(got, want)
+
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (ONLINE, "f16")])
+def test_uniform_scores_give_the_mean_of_values(variant, dtype):
+    w = synthetic.small("t", 1, 2, 1, 40, 333, 128, dtype, False, seed=4001)
+    q, k, v, _ = synthetic.make_qkv(w)
+    q = torch.zeros_like(q)
+    got = run_flashd(q, k, v, False, w.scale, variant, 1)
+    mean = v.double().mean(dim=2, keepdim=True).expand(-1, 2, 40, -1).numpy()
+    check(got, mean, DT[dtype])
+    check(got, oracle(q, k, v, False, w.scale), DT[dtype])
+
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (PER_KEY, "f16")])
+def test_key_permutation_invariance(variant, dtype):
+    w = synthetic.small("t", 1, 2, 2, 130, 300, 64, dtype, False, seed=4002)
+    q, k, v, _ = synthetic.make_qkv(w)
+    perm = torch.from_numpy(np.random.default_rng(1).permutation(300))
+    a = run_flashd(q, k, v, False, w.scale, variant, 1)
+    b = run_flashd(q, k[:, :, perm].contiguous(), v[:, :, perm].contiguous(), False, w.scale,
+                   variant, 1)
+    ref = oracle(q, k, v, False, w.scale)
+    check(a, ref, DT[dtype])
+    check(b, ref, DT[dtype])
+
+
+@pytest.mark.parametrize("variant,dtype,d", [(TILE, "f16", 64), (TILE, "bf16", 128),
+                                             (PER_KEY, "f32", 64), (PER_KEY, "f16", 64),
+                                             (ONLINE, "f16", 64)])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_huge_scores_and_dominant_keys_stay_finite_and_right(variant, dtype, d, splits):
+    """Scaled scores of +-hundreds with planted dominant keys (jumps of ~ +-1000 between
+    consecutive scores): no max subtraction on the FLASH-D paths, yet no overflow."""
+    w = synthetic.small("t", 1, 2, 2, 300, 300, d, dtype, True, seed=4003, qk_std=4.0,
+                        plant_frac=0.1)
+    q, k, v, planted = synthetic.make_qkv(w)
+    assert len(planted) > 20
+    ref = oracle(q, k, v, True, w.scale)
+    got = run_flashd(q, k, v, True, w.scale, variant, splits)
+    check(got, ref, DT[dtype], f"stress variant={variant} {dtype}",
+          smax=max_abs_score(q, k, w.scale))
+
+
+def test_score_ramps():
+    """s_j = +-c*j: an ascending ramp keeps only the last key, a descending one the first."""
+    L, d = 200, 64
+    for sign in (+1.0, -1.0):
+        q = torch.zeros(1, 1, 1, d)
+        q[..., 0] = 1.0
+        k = torch.zeros(1, 1, L, d)
+        k[0, 0, :, 0] = sign * 40.0 * torch.arange(L)
+        v = torch.from_numpy(np.random.default_rng(2).standard_normal((1, 1, L, d))).float()
+        for dtype, variant in ((torch.float32, PER_KEY), (torch.bfloat16, TILE),
+                               (torch.bfloat16, PER_KEY)):
+            qq, kk, vv = q.to(dtype), k.to(dtype), v.to(dtype)
+            got = run_flashd(qq, kk, vv, False, 1.0, variant, 1)
+            want = vv[0, 0, -1 if sign > 0 else 0]
+            if dtype == torch.float32:      # o + (v - o) * 1 may differ from v by an ulp
+                assert torch.allclose(got[0, 0, 0], want, rtol=3e-7, atol=1e-7)
+            else:
+                assert torch.equal(got[0, 0, 0], want)
+
+
+# ----------------------------------------------------------------- mask and heads ---
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (PER_KEY, "bf16"),
+                                           (ONLINE, "bf16")])
+def test_causal_mask_is_bit_exact_under_junk_in_masked_positions(variant, dtype):
+    Lq, Lk, d = 200, 230, 64            # off = 30
+    w = synthetic.small("t", 1, 2, 1, Lq, Lk, d, dtype, True, seed=4004)
+    q, k, v, _ = synthetic.make_qkv(w)
+    base = run_flashd(q, k, v, True, w.scale, variant, 1)
+    for jstar in (31, 64, 100, 191, 229):
+        k2, v2 = k.clone(), v.clone()
+        k2[:, :, jstar:, :] = 3.0e4 if dtype != "f16" else 6.0e4
+        v2[:, :, jstar:, :] = -2.5e4
+        junk = run_flashd(q, k2, v2, True, w.scale, variant, 1)
+        first_seeing = jstar - (Lk - Lq)            # row i sees key j iff j <= i + 30
+        assert torch.equal(junk[:, :, :first_seeing], base[:, :, :first_seeing])
+        assert not torch.equal(junk[:, :, first_seeing:], base[:, :, first_seeing:])
+
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (ONLINE, "f16")])
+@pytest.mark.parametrize("Lq,Lk", [(64, 64), (40, 64), (64, 40)])
+def test_identity_values_expose_the_weight_row(variant, dtype, Lq, Lk):
+    d = 64
+    w = synthetic.small("t", 1, 1, 1, Lq, Lk, d, dtype, True, seed=4005)
+    q, k, v, _ = synthetic.make_qkv(w)
+    v = torch.zeros_like(v)
+    v[0, 0, :, :Lk] = torch.eye(Lk, dtype=v.dtype)
+    got = run_flashd(q, k, v, True, w.scale, variant, 1)[0, 0].double().numpy()
+    ref = oracle(q, k, v, True, w.scale)[0, 0]
+    for i in range(Lq):
+        for j in range(Lk):
+            if j > i + (Lk - Lq):
+                assert got[i, j] == 0.0 and ref[i, j] == 0.0
+    assert np.array_equal(got != 0, ref != 0) or dtype == "f16"     # tiny weights may flush
+    check(torch.from_numpy(got), ref, DT[dtype])
+
+
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (ONLINE, "bf16")])
+def test_gqa_head_mapping(variant, dtype):
+    w = synthetic.small("t", 2, 8, 2, 33, 90, 128, dtype, False, seed=4006)
+    q, k, v, _ = synthetic.make_qkv(w)
+    v[:, 1] = 3.25
+    got = run_flashd(q, k, v, False, w.scale, variant, 1).float()
+    assert torch.all((got[:, 4:] - 3.25).abs() <= (0.0 if dtype == "f32" else 0.02))
+    assert not torch.any((got[:, :4] - 3.25).abs() < 1e-2)
+    if dtype == "f32":
+        assert torch.all((got[:, 4:] - 3.25).abs() < 1e-5)
+
+
+def test_output_is_bitwise_reproducible():
+    w = synthetic.small("t", 2, 4, 2, 300, 500, 128, "bf16", True, seed=4007)
+    q, k, v, _ = synthetic.make_qkv(w)
+    for variant, splits in ((TILE, 1), (TILE, 3), (PER_KEY, 2), (ONLINE, 1)):
+        a = run_flashd(q, k, v, True, w.scale, variant, splits)
+        b = run_flashd(q, k, v, True, w.scale, variant, splits)
+        assert torch.equal(a, b)
+
+
+def test_first_config_in_full():
+    w = synthetic.CONFIGS[0]
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, w.causal, w.scale)
+    got = run_flashd(q, k, v, w.causal, w.scale, use_ex=False)
+    err = check(got, ref, torch.float32, "config 1")
+    assert err <= 1e-5 * max(1.0, float(np.abs(ref).max()))
+    assert math.isfinite(err)
