@@ -48,6 +48,8 @@ int auto_splits(const Shape& s, int variant) {
     if (variant == FLASHD_VARIANT_PER_KEY) {
         const int rows_per_group = (s.d <= 64 ? 2 : 1) * 4;             // 4 wavefronts
         units = (long)s.B * s.Hq * ceil_div(s.Lq, rows_per_group);      // workgroups
+    } else if (flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) {
+        units = flashd::decode_workgroups(s.B, s.Hkv);
     } else {
         units = flashd::tile_workgroups(s.B, s.Hq, s.Hkv, s.Lq, s.d);
     }
@@ -150,8 +152,10 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.scale = scale;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
+    const bool online = var == FLASHD_VARIANT_ONLINE_SOFTMAX;
     if (var == FLASHD_VARIANT_PER_KEY) e = flashd::launch_perkey(p, st);
-    else e = flashd::launch_tile(p, var == FLASHD_VARIANT_ONLINE_SOFTMAX, st);
+    else if (flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) e = flashd::launch_decode(p, online, st);
+    else e = flashd::launch_tile(p, online, st);
     return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;
 }
 

@@ -1,0 +1,247 @@
+// Split-K decode (few query rows per kv head, long key range): HBM-bound streaming of K
+// and V, each element read once for all Hq/Hkv query heads of a kv group.
+//
+// A workgroup owns one (b, kv head, key split).  The g * Lq <= 32 query rows that share
+// the kv head become the 32 columns of the score tile S^T = K Q^T, so the register layout
+// and the per-row FLASH-D update are those of the prefill kernel (one lane pair per row).
+// The four wavefronts of the workgroup do not share keys: wavefront w takes the 32-key
+// blocks w, w + 4, ... of the split, stages them through its own LDS region (no workgroup
+// barrier in the loop) and keeps its own state (U, Lam).  At the end the four states are
+// folded with the sigmoid rule -- a run of keys acts as one key of score Lam -- and the
+// result is either the output (splits == 1) or a partial state (o, s, ln w) for the merge
+// kernel.
+//
+// Memory pipeline: each lane fetches the next block's K and V with fully coalesced 16-byte
+// loads (a block is one contiguous 32 * d * 2 byte range) into registers while the
+// current block is being multiplied; V stays row-major in LDS and is read through the
+// transposing LDS load.
+#include "flashd_common.h"
+#include "flashd_kernels.h"
+#include "flashd_mma.h"
+
+namespace flashd {
+
+constexpr int kDecWaves = 4;
+constexpr int kDecThreads = kDecWaves * kWave;
+constexpr int kDecBlock = 32;      // keys per wavefront step
+
+// Issue the coalesced 16-byte loads of one 32-key block of K and V into registers.
+template <int D, int CH>
+__device__ __forceinline__ void fetch_block(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
+                                            int lane, u32x4 (&kreg)[CH], u32x4 (&vreg)[CH]) {
+#pragma unroll
+    for (int n = 0; n < CH; ++n) {
+        const int c = n * kWave + lane;            // chunk index inside the block
+        const int key = c / (D / 8);
+        const int part = c % (D / 8);
+        const size_t off = (size_t)min(j0 + key, Lk - 1) * D + 8 * part;
+        kreg[n] = *reinterpret_cast<const u32x4*>(kg + off);
+        vreg[n] = *reinterpret_cast<const u32x4*>(vg + off);
+    }
+}
+
+template <typename T, int D, bool ONLINE>
+__global__ __launch_bounds__(kDecThreads, 2)
+void decode_kernel(Problem p) {
+    constexpr int KROW = D + 8;                 // padded LDS rows (elements)
+    constexpr int VROW = D + 8;
+    constexpr int NKK = D / 16;
+    constexpr int NDB = D / 32;
+    constexpr int CH = kDecBlock * D / 8 / kWave;      // 16-byte chunks per lane per block
+    constexpr int STAGE = kDecBlock * (KROW + VROW);   // elements per wavefront
+    __shared__ __align__(16) uint16_t lds[kDecWaves * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int col = lane & 31;
+    const int hh = lane >> 5;
+    const int sp = blockIdx.x;
+    const int kvh = blockIdx.y;
+    const int b = blockIdx.z;
+    const int g = p.Hq / p.Hkv;
+    const int nrows = g * p.Lq;                 // <= 32, checked by the launcher
+
+    // query row of this lane's column: head kvh * g + col / Lq, position col % Lq
+    const bool row_ok = col < nrows;
+    const int head = kvh * g + (row_ok ? col / p.Lq : 0);
+    const int qi = row_ok ? col % p.Lq : 0;
+    const uint16_t* qg = static_cast<const uint16_t*>(p.q) +
+                         (((size_t)b * p.Hq + head) * (size_t)p.Lq + qi) * D;
+    uint4 qf[NKK];
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+        qf[kk] = row_ok ? *reinterpret_cast<const uint4*>(qg + 16 * kk + 8 * hh)
+                        : make_uint4(0u, 0u, 0u, 0u);
+    }
+    // position 0 sees the fewest keys, position Lq - 1 the most; unused columns (zero
+    // query, output discarded) mimic the last position so they never leave the fast path
+    const int nvis_min = visible_count(p, 0);
+    const int nvis_max = visible_count(p, p.Lq - 1);
+    const int nvis = row_ok ? visible_count(p, qi) : nvis_max;
+
+    const uint16_t* kg = static_cast<const uint16_t*>(p.k) +
+                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
+    const uint16_t* vg = static_cast<const uint16_t*>(p.v) +
+                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
+
+    // 32-key blocks of this split; wavefront w takes blk_begin + w, + 4, ...
+    const int nblk = (nvis_max + kDecBlock - 1) / kDecBlock;
+    const int nblk_all = (p.Lk + kDecBlock - 1) / kDecBlock;
+    const int per_split = (nblk_all + p.splits - 1) / p.splits;
+    const int blk_begin = sp * per_split;
+    const int blk_end = min(nblk, blk_begin + per_split);
+
+    uint16_t* ks = lds + wave * STAGE;
+    uint16_t* vs = ks + kDecBlock * KROW;
+
+    const float c_log2 = p.scale * kLog2e;
+    const float ninf = -__builtin_inff();
+    f32x16 U[NDB];
+#pragma unroll
+    for (int i = 0; i < NDB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) U[i][r] = 0.0f;
+    float lam = ninf;
+    float beta = ONLINE ? 0.0f : 1.0f;
+
+    u32x4 kreg[CH], vreg[CH];      // native vectors: HIP's uint4 struct would live in scratch
+    int blk = blk_begin + wave;
+    if (blk < blk_end) fetch_block<D, CH>(kg, vg, blk * kDecBlock, p.Lk, lane, kreg, vreg);
+    while (blk < blk_end) {
+        const int j0 = blk * kDecBlock;
+        // registers -> this wavefront's LDS stage
+#pragma unroll
+        for (int n = 0; n < CH; ++n) {
+            const int c = n * kWave + lane;
+            const int key = c / (D / 8);
+            const int part = c % (D / 8);
+            *reinterpret_cast<u32x4*>(&ks[key * KROW + 8 * part]) = kreg[n];
+            *reinterpret_cast<u32x4*>(&vs[key * VROW + 8 * part]) = vreg[n];
+        }
+        const int nxt = blk + kDecWaves;
+        if (nxt < blk_end)                             // in flight during the math below
+            fetch_block<D, CH>(kg, vg, nxt * kDecBlock, p.Lk, lane, kreg, vreg);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // S^T = K Q^T for the block's 32 keys
+        f32x16 acc[1];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][r] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+            const uint4 a = *reinterpret_cast<const uint4*>(&ks[col * KROW + 16 * kk + 8 * hh]);
+            acc[0] = Mma<T>::mfma(a, qf[kk], acc[0]);
+        }
+        const bool need_mask = j0 + kDecBlock > nvis_min;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float s = acc[0][r] * c_log2;
+            if (need_mask) {
+                const int j = j0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                if (j >= nvis) s = ninf;
+            }
+            acc[0][r] = s;
+        }
+        const float f = row_step<T, 1, ONLINE>(acc, lam, beta);
+
+#pragma unroll
+        for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) U[i][r] *= f;
+#pragma unroll
+        for (int g2 = 0; g2 < 2; ++g2) {
+            f32x8 pv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv[e] = acc[0][8 * g2 + e];
+            const uint4 bfrag = Mma<T>::pack8(pv);
+#pragma unroll
+            for (int i = 0; i < NDB; ++i) {
+                const uint4 a = lds_read_v_operand(&vs[(16 * g2) * VROW + 32 * i], VROW, lane);
+                U[i] = Mma<T>::mfma(a, bfrag, U[i]);
+            }
+        }
+        // the next stage write must not overtake these LDS reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        blk = nxt;
+    }
+
+    // ---- fold the four wavefront states (sigmoid rule on runs of keys) --------------
+    float fin, lam_out;
+    row_finish<ONLINE>(lam, beta, fin, lam_out);
+    __syncthreads();                                   // stages are dead, reuse the LDS
+    float* st = reinterpret_cast<float*>(lds);         // [wave][row][D + 1]
+    constexpr int SROW = D + 1;
+    if (row_ok) {
+        float* dst = st + ((size_t)wave * 32 + col) * SROW;
+#pragma unroll
+        for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                dst[32 * i + 8 * (r >> 2) + 4 * hh + (r & 3)] = U[i][r] * fin;
+        if (hh == 0) dst[D] = lam_out;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nrows * D; idx += kDecThreads) {
+        const int row = idx / D;
+        const int t = idx % D;
+        float o = 0.0f;
+        float lm = ninf;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) {
+            const float* src = st + ((size_t)w * 32 + row) * SROW;
+            const float lb = src[D];
+            if (lb == ninf) continue;                  // empty run: identity
+            if (lm == ninf) { o = src[t]; lm = lb; continue; }
+            // W = sigmoid(Lam_b - Lam_a) in log2 units; o += (o_b - o) W; Lam = lse
+            const float dlt = lb - lm;
+            const float e = exp2_fast(-fabsf(dlt));
+            const float r1 = __builtin_amdgcn_rcpf(1.0f + e);
+            const float W = dlt >= 0.0f ? r1 : e * r1;
+            o = fmaf(src[t] - o, W, o);
+            lm = fmaxf(lm, lb) + log2_fast(1.0f + e);
+        }
+        const int hq = kvh * g + row / p.Lq;
+        const int i = row % p.Lq;
+        const size_t orow = ((size_t)b * p.Hq + hq) * (size_t)p.Lq + i;
+        if (p.splits == 1) {
+            Store<T>::store(p.o, orow * D + t, o);
+        } else {
+            float* dst = p.ws + ((size_t)sp * p.B * p.Hq * p.Lq + orow) * (D + 2);
+            dst[t] = o;
+            if (t == 0) { dst[D] = lm * kLn2; dst[D + 1] = 0.0f; }
+        }
+    }
+}
+
+template <typename T, int D>
+static hipError_t launch_decode_t(const Problem& p, bool online, hipStream_t st) {
+    dim3 grid((unsigned)p.splits, (unsigned)p.Hkv, (unsigned)p.B);
+    if (online)
+        hipLaunchKernelGGL((decode_kernel<T, D, true>), grid, dim3(kDecThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((decode_kernel<T, D, false>), grid, dim3(kDecThreads), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits == 1) return e;
+    return launch_merge_splits(p, st);
+}
+
+bool decode_applies(int Hq, int Hkv, int Lq) {
+    return (long)(Hq / Hkv) * Lq <= 32;
+}
+
+long decode_workgroups(int B, int Hkv) { return (long)B * Hkv; }
+
+hipError_t launch_decode(const Problem& p, bool online, hipStream_t st) {
+    if (!decode_applies(p.Hq, p.Hkv, p.Lq)) return hipErrorInvalidValue;
+    if (p.dtype == 1 && p.d == 64) return launch_decode_t<F16, 64>(p, online, st);
+    if (p.dtype == 1 && p.d == 128) return launch_decode_t<F16, 128>(p, online, st);
+    if (p.dtype == 2 && p.d == 64) return launch_decode_t<BF16, 64>(p, online, st);
+    if (p.dtype == 2 && p.d == 128) return launch_decode_t<BF16, 128>(p, online, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace flashd

@@ -21,4 +21,10 @@ hipError_t launch_tile(const Problem& p, bool online, hipStream_t st);
 // Number of workgroups launch_tile uses per split.
 long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d);
 
+// Split-K decode on the matrix cores for (Hq / Hkv) * Lq <= 32 query rows per kv head
+// (f16/bf16); online = the Alg. 2 ablation.  With p.splits > 1 also folds the partials.
+hipError_t launch_decode(const Problem& p, bool online, hipStream_t st);
+bool decode_applies(int Hq, int Hkv, int Lq);
+long decode_workgroups(int B, int Hkv);
+
 }  // namespace flashd

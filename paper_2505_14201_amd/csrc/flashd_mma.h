@@ -1,0 +1,193 @@
+// Matrix-core building blocks shared by the tiled prefill and the decode kernels:
+// the v_mfma_f32_32x32x16 wrappers per storage type, and the per-row update of the
+// FLASH-D state for one tile of keys (plus the Alg. 2 update used by the ablation).
+//
+// Register layout this file assumes (checked on gfx950 with an integer-valued probe):
+// for D = A B with A 32xK, B Kx32 (K = 16), lane l = (c, hh) = (l % 32, l / 32) supplies
+// A[c][8 hh .. 8 hh + 7] and B[8 hh .. 8 hh + 7][c], and receives D[8 (r / 4) + 4 hh + r % 4][c]
+// in accumulator register r = 0..15.
+#pragma once
+
+#include "flashd_common.h"
+
+namespace flashd {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <typename T> struct Mma;
+template <> struct Mma<BF16> {
+    // log2 units: 2^{s - Lam} <= 2^60, and 64 of them times |v|, stay far below fp32 overflow
+    static constexpr float kTheta = 60.0f;
+    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
+        return __builtin_bit_cast(uint4, __builtin_convertvector(x, bf16x8));
+    }
+};
+template <> struct Mma<F16> {
+    static constexpr float kTheta = 14.0f;      // 2^14 is representable in fp16
+    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
+        return __builtin_bit_cast(uint4, __builtin_convertvector(x, f16x8));
+    }
+};
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
+
+// log2(2^a + 2^b) through 2^{-|a-b|} <= 1 (the saturating side of the sigmoid);
+// -inf is the empty run.
+__device__ __forceinline__ float lse2(float a, float b) {
+    const float ninf = -__builtin_inff();
+    if (a == ninf) return b;
+    if (b == ninf) return a;
+    return fmaxf(a, b) + log2_fast(1.0f + exp2_fast(-fabsf(a - b)));
+}
+
+// 8 keys x 1 column of a row-major [key][d] LDS tile as an MFMA operand, through the
+// transposing LDS read: within each 16-lane group, lanes 4r .. 4r+3 address the four
+// 8-byte pieces of row r (r = 0..3) and lane t receives column t of those four rows.
+// `base` points at element [key0][dcol0]; rows are `row_elems` apart.  Lane (c, hh)
+// receives keys key0 + 4 hh + {0..3} and key0 + 8 + 4 hh + {0..3} at column dcol0 + c,
+// which is the key order of the score accumulator registers r = 0..7 (see above).
+__device__ __forceinline__ uint4 lds_read_v_operand(const uint16_t* base, int row_elems, int lane) {
+    const int t = lane & 15;
+    const int hh = lane >> 5;
+    const int half = (lane >> 4) & 1;
+    const uint16_t* p0 = base + (4 * hh + (t >> 2)) * row_elems + 16 * half + 4 * (t & 3);
+    const uint16_t* p1 = p0 + 8 * row_elems;
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
+    uint4 r;
+    r.x = __builtin_bit_cast(uint2, lo).x; r.y = __builtin_bit_cast(uint2, lo).y;
+    r.z = __builtin_bit_cast(uint2, hi).x; r.w = __builtin_bit_cast(uint2, hi).y;
+    return r;
+}
+
+// One tile of keys for one query row.  On entry acc[][] holds the row's scores in log2
+// units (masked keys: -inf) in the accumulator layout, the row being shared by lanes l
+// and l ^ 32.  On exit acc[][] holds the coefficients p_j to be rounded and multiplied
+// with V; the return value is the factor the row's accumulator U must be scaled by BEFORE
+// p V is added.  State:
+//   FLASH-D (ONLINE = false): lam = Lam = s_last - ln w_last in log2 units (-inf: no key
+//     yet); beta = factor still owed to U (true o = beta U).
+//   Alg. 2  (ONLINE = true):  lam = running max m, beta = running sum l (o = U / l).
+template <typename T, int NB, bool ONLINE>
+__device__ __forceinline__ float row_step(f32x16 (&acc)[NB], float& lam, float& beta) {
+    const float ninf = -__builtin_inff();
+    float f;
+    if (!ONLINE) {
+        // A row is "risky" when one of its scores exceeds Lam by more than kTheta, or Lam
+        // is still -inf (its first visible tile): then 2^{s - Lam} is not formed.  The
+        // choice is per row, so a row's result never depends on other rows' data.
+        bool risky = false;
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) risky |= !(acc[kb][r] - lam <= Mma<T>::kTheta);
+        risky |= (__shfl_xor((int)risky, 32, 64) != 0);
+        float ref = lam;          // exponent reference of this row for this tile
+        float lam_new = lam;
+        if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+            // key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j -
+            // Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as
+            // Lam = s - ln w; the first visible key starts the run (w = 1).  The sigmoid
+            // saturates instead of overflowing, whatever the score jump (Sec. III-C).
+            float ll = ninf;
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float s = acc[kb][r];
+                    if (s != ninf) ll = lse2(ll, s);
+                }
+            ll = lse2(ll, __shfl_xor(ll, 32, 64));      // partner lane's run
+            lam_new = lse2(lam, ll);                      // the tile acts as one key
+            if (risky) ref = (lam_new == ninf) ? 0.0f : lam_new;
+        }
+        float psum = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pj = exp2_fast(acc[kb][r] - ref);
+                psum += pj;
+                acc[kb][r] = pj;
+            }
+        psum += __shfl_xor(psum, 32, 64);
+        if (!risky) {
+            // tile rule: p_j = 2^{s_j - Lam}, tot = 1 + sum p_j, 1 - W = 1/tot
+            const float tot = 1.0f + psum;
+            f = beta;
+            beta = __builtin_amdgcn_rcpf(tot);
+            lam += log2_fast(tot);
+        } else {
+            // c_j = 2^{s_j - Lam_new} <= 1 is already final; the old state decays by
+            // 2^{Lam - Lam_new} = 1 - W
+            const float decay = (lam == ninf) ? 0.0f : exp2_fast(lam - lam_new);
+            f = beta * decay;
+            beta = 1.0f;
+            lam = lam_new;
+        }
+    } else {
+        // Alg. 2: m_i = max(m_{i-1}, s), l_i = l_{i-1} e^{m_{i-1}-m_i} + sum e^{s-m_i}
+        float mx = ninf;
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[kb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(lam, mx);
+        const float m_use = (m_new == ninf) ? 0.0f : m_new;
+        const float resc = exp2_fast(lam - m_use);
+        float psum = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pj = exp2_fast(acc[kb][r] - m_use);
+                psum += pj;
+                acc[kb][r] = pj;
+            }
+        psum += __shfl_xor(psum, 32, 64);
+        beta = beta * resc + psum;
+        lam = m_new;
+        f = resc;
+    }
+    return f;
+}
+
+// What a finished row hands on: the factor that turns U into the output, and the row's
+// Lam (log2 units) for a later merge with other key ranges.
+template <bool ONLINE>
+__device__ __forceinline__ void row_finish(float lam, float beta, float& fin, float& lam_out) {
+    if (!ONLINE) {
+        fin = beta;                 // FLASH-D: the state is the output
+        lam_out = lam;
+    } else {
+        fin = beta > 0.0f ? 1.0f / beta : 0.0f;      // the one division of Alg. 2
+        lam_out = beta > 0.0f ? lam + log2_fast(beta) : -__builtin_inff();
+    }
+}
+
+__device__ __forceinline__ int visible_count(const Problem& p, int i) {
+    if (i >= p.Lq) return 0;
+    if (!p.causal) return p.Lk;
+    return min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
+}
+
+}  // namespace flashd

@@ -25,58 +25,13 @@
 // keys permuted to match that operand order.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
+#include "flashd_mma.h"
 
 namespace flashd {
-
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kBC = 64;           // keys per tile
 constexpr int kTileThreads = 256;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-template <typename T> struct Mma;
-template <> struct Mma<BF16> {
-    static constexpr float kTheta = 60.0f;      // log2 units; p_j <= 2^60 stays far from fp32 overflow
-    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
-        return __builtin_bit_cast(uint4, __builtin_convertvector(x, bf16x8));
-    }
-};
-template <> struct Mma<F16> {
-    static constexpr float kTheta = 14.0f;      // p_j <= 2^14 is representable in fp16
-    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
-        return __builtin_bit_cast(uint4, __builtin_convertvector(x, f16x8));
-    }
-};
-
-__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
-
-// log2(2^a + 2^b) through 2^{-|a-b|} <= 1; -inf is the empty run.
-__device__ __forceinline__ float lse2(float a, float b) {
-    const float ninf = -__builtin_inff();
-    if (a == ninf) return b;
-    if (b == ninf) return a;
-    return fmaxf(a, b) + log2_fast(1.0f + exp2_fast(-fabsf(a - b)));
-}
-
-__device__ __forceinline__ int visible_count(const Problem& p, int i) {
-    if (i >= p.Lq) return 0;
-    if (!p.causal) return p.Lk;
-    return min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
-}
 
 template <typename T, int D, bool ONLINE>
 __global__ __launch_bounds__(kTileThreads, 2)
@@ -217,85 +172,8 @@ void tile_kernel(Problem p) {
                 acc[kb][r] = s;
             }
 
-        float f;      // factor applied to U before this tile's products are added
-        if (!ONLINE) {
-            // A row is "risky" when one of its scores exceeds Lam by more than kTheta, or
-            // Lam is still -inf (first visible tile): then 2^{s - Lam} is not formed.  The
-            // choice is per row, so a row's result never depends on other rows' data.
-            bool risky = false;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) risky |= !(acc[kb][r] - lam <= Mma<T>::kTheta);
-            risky |= (__shfl_xor((int)risky, 32, 64) != 0);
-            float ref = lam;          // exponent reference of this row for this tile
-            float lam_new = lam;
-            if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-                // key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j -
-                // Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as
-                // Lam = s - ln w; the first visible key starts the run (w = 1).  The sigmoid
-                // saturates instead of overflowing, whatever the score jump.
-                float ll = ninf;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float s = acc[kb][r];
-                        if (s != ninf) ll = lse2(ll, s);
-                    }
-                ll = lse2(ll, __shfl_xor(ll, 32, 64));      // partner lane's run
-                lam_new = lse2(lam, ll);                      // the tile acts as one key
-                if (risky) ref = (lam_new == ninf) ? 0.0f : lam_new;
-            }
-            float psum = 0.0f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pj = exp2_fast(acc[kb][r] - ref);
-                    psum += pj;
-                    acc[kb][r] = pj;
-                }
-            psum += __shfl_xor(psum, 32, 64);
-            if (!risky) {
-                // tile rule: p_j = 2^{s_j - Lam}, tot = 1 + sum p_j, 1 - W = 1/tot
-                const float tot = 1.0f + psum;
-                f = beta;
-                beta = __builtin_amdgcn_rcpf(tot);
-                lam += log2_fast(tot);
-            } else {
-                // c_j = 2^{s_j - Lam_new} <= 1 already final; the old state decays by
-                // 2^{Lam - Lam_new} = 1 - W
-                const float decay = (lam == ninf) ? 0.0f : exp2_fast(lam - lam_new);
-                f = beta * decay;
-                beta = 1.0f;
-                lam = lam_new;
-            }
-        } else {
-            // Alg. 2: m_i = max(m_{i-1}, s), l_i = l_{i-1} e^{m_{i-1}-m_i} + sum e^{s-m_i}
-            float mx = ninf;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[kb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(lam, mx);
-            const float m_use = (m_new == ninf) ? 0.0f : m_new;
-            const float resc = exp2_fast(lam - m_use);
-            float psum = 0.0f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pj = exp2_fast(acc[kb][r] - m_use);
-                    psum += pj;
-                    acc[kb][r] = pj;
-                }
-            psum += __shfl_xor(psum, 32, 64);
-            beta = beta * resc + psum;
-            lam = m_new;
-            f = resc;
-        }
+        // ---- per-row state update; acc becomes the coefficients p_j
+        const float f = row_step<T, 2, ONLINE>(acc, lam, beta);
 
         // ---- U <- f U + P V   (O^T = V^T P^T)
 #pragma unroll
@@ -320,15 +198,8 @@ void tile_kernel(Problem p) {
     if (my_row >= p.Lq) return;
     // ---- epilogue.  FLASH-D: the output is the state (times the factor still owed);
     // ONLINE: the one division of Alg. 2.
-    float fin;
-    float lam_out;
-    if (!ONLINE) {
-        fin = beta;
-        lam_out = lam;
-    } else {
-        fin = beta > 0.0f ? 1.0f / beta : 0.0f;
-        lam_out = beta > 0.0f ? lam + log2_fast(beta) : ninf;
-    }
+    float fin, lam_out;
+    row_finish<ONLINE>(lam, beta, fin, lam_out);
     if (p.splits == 1) {
         uint16_t* og = static_cast<uint16_t*>(p.o) +
                        (((size_t)b * p.Hq + h) * (size_t)p.Lq + my_row) * D;

@@ -76,6 +76,25 @@ def test_split_k_partials_merge_to_the_same_result(variant, splits, causal):
         check(got, ref, DT[dtype], f"splits={splits} variant={variant} Lq={Lq} Lk={Lk}")
 
 
+@pytest.mark.parametrize("variant", [TILE, ONLINE])
+@pytest.mark.parametrize("splits", [1, 2, 5, 0])
+def test_decode_shapes(variant, splits):
+    """(Hq / Hkv) * Lq <= 32 query rows per kv head take the split-K decode kernel."""
+    for (B, Hq, Hkv, Lq, Lk, d, dtype, causal) in [
+            (3, 32, 8, 1, 3000, 128, "bf16", False),     # the GQA decode shape, shortened
+            (1, 8, 1, 4, 500, 128, "bf16", True),        # exactly 32 rows, causal positions
+            (2, 4, 4, 7, 333, 64, "f16", True),          # no GQA, several positions
+            (1, 16, 2, 2, 31, 64, "bf16", False),        # less than one 32-key block
+            (1, 2, 2, 9, 5, 128, "f16", True)]:          # Lq > Lk: rows without any key
+        w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=3300 + Lk + splits)
+        q, k, v, _ = synthetic.make_qkv(w)
+        ref = oracle(q, k, v, causal, w.scale)
+        if splits > Lk:
+            continue
+        got = run_flashd(q, k, v, causal, w.scale, variant, splits)
+        check(got, ref, DT[dtype], f"decode splits={splits} variant={variant} Lq={Lq} Lk={Lk}")
+
+
 def test_split_k_f32_and_more_splits_than_tiles():
     w = synthetic.small("t", 1, 2, 1, 4, 130, 64, "f32", False, seed=3100)
     q, k, v, _ = synthetic.make_qkv(w)
