@@ -44,7 +44,7 @@ template <typename T, int D, bool ONLINE>
 __global__ __launch_bounds__(kDecThreads, 2)
 void decode_kernel(Problem p) {
     constexpr int KROW = D + 8;                 // padded LDS rows (elements)
-    constexpr int VROW = D + 8;
+    constexpr int VROW = D + 32;                // conflict-free for the transposing read
     constexpr int NKK = D / 16;
     constexpr int NDB = D / 32;
     constexpr int CH = kDecBlock * D / 8 / kWave;      // 16-byte chunks per lane per block
@@ -68,11 +68,11 @@ void decode_kernel(Problem p) {
     const int qi = row_ok ? col % p.Lq : 0;
     const uint16_t* qg = static_cast<const uint16_t*>(p.q) +
                          (((size_t)b * p.Hq + head) * (size_t)p.Lq + qi) * D;
-    uint4 qf[NKK];
+    u32x4 qf[NKK];
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
-        qf[kk] = row_ok ? *reinterpret_cast<const uint4*>(qg + 16 * kk + 8 * hh)
-                        : make_uint4(0u, 0u, 0u, 0u);
+        qf[kk] = row_ok ? *reinterpret_cast<const u32x4*>(qg + 16 * kk + 8 * hh)
+                        : u32x4{0u, 0u, 0u, 0u};
     }
     // position 0 sees the fewest keys, position Lq - 1 the most; unused columns (zero
     // query, output discarded) mimic the last position so they never leave the fast path
@@ -132,7 +132,7 @@ void decode_kernel(Problem p) {
         for (int r = 0; r < 16; ++r) acc[0][r] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-            const uint4 a = *reinterpret_cast<const uint4*>(&ks[col * KROW + 16 * kk + 8 * hh]);
+            const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[col * KROW + 16 * kk + 8 * hh]);
             acc[0] = Mma<T>::mfma(a, qf[kk], acc[0]);
         }
         const bool need_mask = j0 + kDecBlock > nvis_min;
@@ -156,10 +156,10 @@ void decode_kernel(Problem p) {
             f32x8 pv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) pv[e] = acc[0][8 * g2 + e];
-            const uint4 bfrag = Mma<T>::pack8(pv);
+            const u32x4 bfrag = Mma<T>::pack8(pv);
 #pragma unroll
             for (int i = 0; i < NDB; ++i) {
-                const uint4 a = lds_read_v_operand(&vs[(16 * g2) * VROW + 32 * i], VROW, lane);
+                const u32x4 a = lds_read_v_operand(&vs[(16 * g2) * VROW + 32 * i], VROW, lane);
                 U[i] = Mma<T>::mfma(a, bfrag, U[i]);
             }
         }

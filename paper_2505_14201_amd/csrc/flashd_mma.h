@@ -18,6 +18,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -26,22 +28,22 @@ template <typename T> struct Mma;
 template <> struct Mma<BF16> {
     // log2 units: 2^{s - Lam} <= 2^60, and 64 of them times |v|, stay far below fp32 overflow
     static constexpr float kTheta = 60.0f;
-    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
-        return __builtin_bit_cast(uint4, __builtin_convertvector(x, bf16x8));
+    static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
+        return __builtin_bit_cast(u32x4, __builtin_convertvector(x, bf16x8));
     }
 };
 template <> struct Mma<F16> {
     static constexpr float kTheta = 14.0f;      // 2^14 is representable in fp16
-    static __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ uint4 pack8(f32x8 x) {
-        return __builtin_bit_cast(uint4, __builtin_convertvector(x, f16x8));
+    static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
+        return __builtin_bit_cast(u32x4, __builtin_convertvector(x, f16x8));
     }
 };
 
@@ -63,7 +65,7 @@ __device__ __forceinline__ float lse2(float a, float b) {
 // `base` points at element [key0][dcol0]; rows are `row_elems` apart.  Lane (c, hh)
 // receives keys key0 + 4 hh + {0..3} and key0 + 8 + 4 hh + {0..3} at column dcol0 + c,
 // which is the key order of the score accumulator registers r = 0..7 (see above).
-__device__ __forceinline__ uint4 lds_read_v_operand(const uint16_t* base, int row_elems, int lane) {
+__device__ __forceinline__ u32x4 lds_read_v_operand(const uint16_t* base, int row_elems, int lane) {
     const int t = lane & 15;
     const int hh = lane >> 5;
     const int half = (lane >> 4) & 1;
@@ -72,10 +74,9 @@ __device__ __forceinline__ uint4 lds_read_v_operand(const uint16_t* base, int ro
     typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
-    uint4 r;
-    r.x = __builtin_bit_cast(uint2, lo).x; r.y = __builtin_bit_cast(uint2, lo).y;
-    r.z = __builtin_bit_cast(uint2, hi).x; r.w = __builtin_bit_cast(uint2, hi).y;
-    return r;
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo);
+    const u32x2 h2 = __builtin_bit_cast(u32x2, hi);
+    return u32x4{l2[0], l2[1], h2[0], h2[1]};
 }
 
 // One tile of keys for one query row.  On entry acc[][] holds the row's scores in log2
@@ -169,6 +170,118 @@ __device__ __forceinline__ float row_step(f32x16 (&acc)[NB], float& lam, float& 
         f = resc;
     }
     return f;
+}
+
+// ---------------------------------------------------------------------------
+// The same tile rule with the blend factor kept as a scalar ("lazy blend"), used by the
+// prefill kernel.  A row's state is (U, R, beta, one):
+//     true output o = beta U,   Lam = R - log2 beta,   one = 0 until the row has seen a key.
+// For a tile, with p_j = 2^{s_j - R} (R does not move on this path) and psum = sum_j p_j,
+//     tot = one + beta psum,   1 - W = 1/tot   (W = sigmoid(S_tile - Lam), the tile's weight),
+//     U <- U + sum_j p_j v_j,  beta <- beta (1 - W).
+// This is o <- (1 - W)(o + sum_j 2^{s_j - Lam} v_j) with the vector multiplication by
+// (1 - W) folded into the scalar beta: U is never rescaled here.  An empty row takes the
+// score of the tile's first key as R (w_1 = 1 for that key).
+//
+// lazy_spec() does that speculatively and reports rows whose psum left the safe range
+// (some 2^{s_j - R} too large for the storage type: a score far above everything before
+// it).  For those rows lazy_rereference() redoes the tile from the raw scores with the
+// key-by-key sigmoid recurrence, which saturates instead of overflowing, and moves R.
+struct LazyRow {
+    float R;      // exponent reference, log2 units
+    float beta;   // o = beta * U
+    float one;    // 0.0f while the row is empty, then 1.0f
+};
+
+template <typename T> struct LazyLimit;
+template <> struct LazyLimit<BF16> { static constexpr float kMaxPsum = 1.0e18f; };   // ~2^60
+template <> struct LazyLimit<F16> { static constexpr float kMaxPsum = 16384.0f; };   // each p_j < 2^14
+
+// acc: raw dot products in the accumulator layout -> coefficients p_j.  jb = index of the
+// key held in register 0 of block 0 by this lane (tile start + 4 hh).  Returns true if the
+// row is risky; in that case the state is left untouched.
+template <typename T, int NB>
+__device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float c_log2,
+                                          bool need_mask, int jb, int nvis, int lane) {
+    const float ninf = -__builtin_inff();
+    const bool empty = st.one == 0.0f;
+    float ref = st.R;
+    if (__builtin_amdgcn_ballot_w64(empty) != 0) {
+        // first key of the tile for this row: register 0 of block 0 in the hh = 0 lane
+        const float s0 = __shfl(acc[0][0], lane & 31, 64) * c_log2;
+        const bool vis0 = (jb - 4 * (lane >> 5)) < nvis;
+        if (empty) ref = vis0 ? s0 : 0.0f;
+    }
+    float psum = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float x = fmaf(acc[kb][r], c_log2, -ref);
+            if (need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
+            const float pj = exp2_fast(x);
+            psum += pj;
+            acc[kb][r] = pj;
+        }
+    psum += __shfl_xor(psum, 32, 64);
+    const bool risky = !(psum <= LazyLimit<T>::kMaxPsum);
+    if (!risky && !(empty && psum == 0.0f)) {
+        const float tot = fmaf(st.beta, psum, st.one);
+        st.beta *= __builtin_amdgcn_rcpf(tot);
+        st.R = ref;
+        st.one = 1.0f;
+    }
+    return risky;
+}
+
+// Re-reference, in three steps so that the caller can recompute the raw scores one 32-key
+// block at a time (acc already holds the speculative p_j):
+//   lazy_chain_block  folds one block's visible scores into the lane's run Lam (ll)
+//   lazy_new_state    folds partner lane and carried state, updates risky rows' state and
+//                     returns the new reference and the factor for U (1 for other rows)
+//   lazy_apply_block  replaces the p_j of risky rows by c_j = 2^{s_j - Lam_new} <= 1
+// Key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j - Lam_{j-1}), i.e.
+// w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the first visible key
+// starts the run (w = 1).  The sigmoid saturates, whatever the jump.
+__device__ __forceinline__ void lazy_chain_block(const f32x16& raw, float& ll, float c_log2,
+                                                 bool need_mask, int jb_blk, int nvis) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const bool masked = need_mask && (jb_blk + 8 * (r >> 2) + (r & 3)) >= nvis;
+        if (!masked) ll = lse2(ll, raw[r] * c_log2);
+    }
+}
+
+__device__ __forceinline__ float lazy_new_state(LazyRow& st, bool risky, float ll, float& ref) {
+    const float ninf = -__builtin_inff();
+    ll = lse2(ll, __shfl_xor(ll, 32, 64));                  // partner lane's run
+    const bool empty = st.one == 0.0f;
+    const float lam_old = empty ? ninf : st.R - log2_fast(st.beta);
+    const float lam_new = lse2(lam_old, ll);                  // the tile acts as one key
+    const bool none = lam_new == ninf;
+    ref = none ? 0.0f : lam_new;
+    float f = 1.0f;
+    if (risky) {
+        // the old state decays by 1 - W = 2^{Lam_old - Lam_new}; it is applied to U now
+        f = empty ? 0.0f : st.beta * exp2_fast(lam_old - lam_new);
+        st.beta = 1.0f;
+        st.R = ref;
+        st.one = none ? 0.0f : 1.0f;
+    }
+    return f;
+}
+
+__device__ __forceinline__ void lazy_apply_block(f32x16& acc, const f32x16& raw, bool risky,
+                                                 float ref, float c_log2, bool need_mask,
+                                                 int jb_blk, int nvis, bool none) {
+    if (!risky) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float x = fmaf(raw[r], c_log2, -ref);
+        const bool masked = need_mask && (jb_blk + 8 * (r >> 2) + (r & 3)) >= nvis;
+        if (masked || none) x = -__builtin_inff();
+        acc[r] = exp2_fast(x);
+    }
 }
 
 // What a finished row hands on: the factor that turns U into the output, and the row's

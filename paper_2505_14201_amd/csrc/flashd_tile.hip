@@ -10,19 +10,28 @@
 //     o <- (1 - W) (o + sum_j p_j v_j),      Lam <- Lam + ln tot,
 // which is the blend o <- (1 - W) o + W o_tile of Sec. III-A with the tile's own
 // weighted value o_tile = sum_j p_j v_j / sum_j p_j.  No maximum is tracked and the
-// output is never divided by a running sum.  Where a score exceeds Lam by more than
-// kTheta (or Lam is still -inf: the first tile) e^{s_j - Lam} is not formed; the tile
-// then runs the recurrence key by key inside each lane (sigmoid saturates instead of
-// overflowing, Sec. III-C) and forms c_j = e^{s_j - Lam_new} <= 1 afterwards.
+// output is not divided by a running sum of exponentials.  The product of the (1 - W)
+// factors is carried as one scalar per row and multiplied in when the row is stored
+// (flashd_mma.h, "lazy blend").  A score far above everything before it would overflow
+// e^{s_j - Lam}; such rows redo the tile with the key-by-key sigmoid recurrence, which
+// saturates instead (Sec. III-C).
 //
-// Mapping.  A workgroup of 4 wavefronts owns 128 query rows of one (b, h); a
-// wavefront owns 32 of them.  Keys stream through LDS in tiles of 64.  The score tile
-// is produced transposed, S^T = K Q^T, by v_mfma_f32_32x32x16: lane (c, hh) =
-// (lane % 32, lane / 32) then holds, for query row c, the 16 keys
-// 8*(r/4) + 4*hh + r%4 (r = 0..15) of each 32-key block, so the whole per-row state
-// lives in that lane and its partner lane ^ 32.  The same registers, rounded to the
-// storage type, are the B operand of O^T = V^T P^T; V is transposed into LDS with the
-// keys permuted to match that operand order.
+// Mapping.  A workgroup of 4 wavefronts owns 128 query rows of one (b, h); a wavefront
+// owns 32 of them.  Keys stream through LDS in tiles of 64, double-buffered: the next
+// tile's global loads are issued before the current tile's math and land in LDS after
+// it, one workgroup barrier per tile.  The score tile is produced transposed,
+// S^T = K Q^T, by v_mfma_f32_32x32x16: lane (c, hh) = (lane % 32, lane / 32) then holds,
+// for query row c, the 16 keys 8*(r/4) + 4*hh + r%4 (r = 0..15) of each 32-key block, so
+// the whole per-row state lives in that lane and its partner lane ^ 32.  The same
+// registers, rounded to the storage type, are the B operand of O^T = V^T P^T; V stays
+// row-major in LDS and its operand comes from the transposing LDS read.  K and V tiles
+// are copied global->LDS directly (no registers), with an XOR chunk swizzle instead of
+// row padding.
+//
+// Launch order: workgroup ids run over (row tile, split, b*Hq + h) with the row tile
+// slowest and, under a causal mask, longest first, so the short tiles fill the tail.
+// Workgroups of one head are B*Hq*splits apart, a multiple of 8 for the usual shapes, and
+// therefore land on the same XCD and share its L2 for K and V.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
@@ -33,15 +42,185 @@ constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kBC = 64;           // keys per tile
 constexpr int kTileThreads = 256;
 
+// LDS layout of one K or V tile: [64 keys][D] elements, rows unpadded (the direct
+// global->LDS loads write 64 consecutive 16-byte chunks per instruction, so rows cannot
+// be padded); bank conflicts are avoided by storing chunk c of row r at chunk position
+// c ^ swz(r).  K is read as 16-byte operands by 16 consecutive keys at a time, V as 8-byte
+// pieces of 4 consecutive keys by the transposing read; each gets the XOR pattern that
+// spreads its access over all banks.
+template <int D> struct TileCfg;
+template <> struct TileCfg<128> {
+    static constexpr int CPR = 16;                                   // chunks per row
+    static __device__ __forceinline__ int swz_k(int row) { return row & 15; }
+    static __device__ __forceinline__ int swz_v(int row) { return 4 * (row & 3); }
+};
+template <> struct TileCfg<64> {
+    static constexpr int CPR = 8;
+    static __device__ __forceinline__ int swz_k(int row) { return (row >> 1) & 7; }
+    static __device__ __forceinline__ int swz_v(int row) { return 4 * ((row >> 1) & 1); }
+};
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Start the direct global->LDS copy of the K and V tiles whose first key is j0.  Every
+// wavefront issues CPR/4 instructions per tensor, each moving 64 chunks of 16 bytes to 1 KB
+// of LDS.  Keys past the end are clamped to the last key (masked later).
+template <int D>
+__device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
+                                         int wave, int lane, uint16_t* ks, uint16_t* vs) {
+    using C = TileCfg<D>;
+#pragma unroll
+    for (int n = 0; n < C::CPR / 4; ++n) {
+        const int inst = wave * (C::CPR / 4) + n;
+        const int slot = inst * 64 + lane;
+        const int row = slot / C::CPR;
+        const int cs = slot % C::CPR;
+        const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
+        __builtin_amdgcn_global_load_lds((gptr_t)(kg + grow + 8 * (cs ^ C::swz_k(row))),
+                                         (lptr_t)(ks + inst * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
+                                         (lptr_t)(vs + inst * 512), 16, 0, 0);
+    }
+}
+
+// raw S^T = K Q^T for one 32-key block of a tile; kaddr[kk] = this lane's element offset
+// of its kk-th operand chunk inside a K tile (block 0)
+template <typename T, int D>
+__device__ __forceinline__ void tile_scores_block(const uint16_t* ks, const u32x4 (&qf)[D / 16],
+                                                  const int (&kaddr)[D / 16], int kb, f32x16& acc) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[kaddr[kk] + 32 * D * kb]);
+        acc = Mma<T>::mfma(a, qf[kk], acc);
+    }
+}
+
+// ... and for both blocks, the two accumulation chains interleaved
+template <typename T, int D>
+__device__ __forceinline__ void tile_scores(const uint16_t* ks, const u32x4 (&qf)[D / 16],
+                                            const int (&kaddr)[D / 16], f32x16 (&acc)[2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[kaddr[kk] + 32 * D * kb]);
+            acc[kb] = Mma<T>::mfma(a, qf[kk], acc[kb]);
+        }
+}
+
+// 8 keys x 1 column of V as an MFMA operand through the transposing LDS read (see
+// flashd_mma.h for the lane roles); vaddr = this lane's element offset for the d-block,
+// key0 = first key of the 16-key group.
+template <int D>
+__device__ __forceinline__ u32x4 tile_v_operand(const uint16_t* vs, int vaddr, int key0) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(vs + vaddr + key0 * D));
+    const s16x4 hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(vs + vaddr + (key0 + 8) * D));
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo);
+    const u32x2 h2 = __builtin_bit_cast(u32x2, hi);
+    return u32x4{l2[0], l2[1], h2[0], h2[1]};
+}
+
+// State that stays in registers for the life of a workgroup's row tile.
+template <int D> struct TileRegs {
+    u32x4 qf[D / 16];
+    int kaddr[D / 16];
+    int vaddr[D / 32];
+    f32x16 U[D / 32];
+    LazyRow st;             // FLASH-D state
+    float lam, beta;        // Alg. 2 state: running max m, running sum l
+};
+
+// One key tile: scores, per-row state update, U += P V.  ks/vs: the tile in LDS.
+template <typename T, int D, bool ONLINE>
+__device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t* vs,
+                                             TileRegs<D>& g, int j0, int hh, int lane, int nvis,
+                                             bool need_mask, float c_log2) {
+    constexpr int NDB = D / 32;
+    const float ninf = -__builtin_inff();
+    f32x16 acc[2];
+    tile_scores<T, D>(ks, g.qf, g.kaddr, acc);
+    const int jb = j0 + 4 * hh;
+
+    if (!ONLINE) {
+        const bool risky = lazy_spec<T, 2>(acc, g.st, c_log2, need_mask, jb, nvis, lane);
+        if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+            // rare: redo the tile for the flagged rows from recomputed raw scores
+            f32x16 raw;
+            float ll = ninf;
+#pragma unroll 1
+            for (int kb = 0; kb < 2; ++kb) {
+                tile_scores_block<T, D>(ks, g.qf, g.kaddr, kb, raw);
+                lazy_chain_block(raw, ll, c_log2, need_mask, jb + 32 * kb, nvis);
+            }
+            float ref;
+            const float f = lazy_new_state(g.st, risky, ll, ref);
+            const bool none = risky && g.st.one == 0.0f;
+#pragma unroll 1
+            for (int kb = 0; kb < 2; ++kb) {
+                tile_scores_block<T, D>(ks, g.qf, g.kaddr, kb, raw);
+                if (kb == 0)
+                    lazy_apply_block(acc[0], raw, risky, ref, c_log2, need_mask, jb, nvis, none);
+                else
+                    lazy_apply_block(acc[1], raw, risky, ref, c_log2, need_mask, jb + 32, nvis,
+                                     none);
+            }
+#pragma unroll
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
+        }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float s = acc[kb][r] * c_log2;
+                if (need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
+                acc[kb][r] = s;
+            }
+        const float f = row_step<T, 2, true>(acc, g.lam, g.beta);
+#pragma unroll
+        for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
+    }
+
+    // ---- U <- U + P V   (O^T = V^T P^T)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+        f32x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pv[e] = acc[g4 >> 1][8 * (g4 & 1) + e];
+        const u32x4 bfrag = Mma<T>::pack8(pv);
+#pragma unroll
+        for (int i = 0; i < NDB; ++i) {
+            const u32x4 a = tile_v_operand<D>(vs, g.vaddr[i], 16 * g4);
+            g.U[i] = Mma<T>::mfma(a, bfrag, g.U[i]);
+        }
+    }
+}
+
 template <typename T, int D, bool ONLINE>
 __global__ __launch_bounds__(kTileThreads, 2)
 void tile_kernel(Problem p) {
-    constexpr int KROW = D + 8;       // padded LDS rows (elements)
-    constexpr int VROW = kBC + 8;
+    using C = TileCfg<D>;
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
-    __shared__ __align__(16) uint16_t ks[kBC * KROW];
-    __shared__ __align__(16) uint16_t vt[D * VROW];
+    // two buffers, as separate objects so that LDS reads of one need not wait for the
+    // asynchronous copy into the other
+    __shared__ __align__(1024) uint16_t k0s[kBC * D];
+    __shared__ __align__(1024) uint16_t v0s[kBC * D];
+    __shared__ __align__(1024) uint16_t k1s[kBC * D];
+    __shared__ __align__(1024) uint16_t v1s[kBC * D];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -49,12 +228,17 @@ void tile_kernel(Problem p) {
     const int col = lane & 31;
     const int hh = lane >> 5;
 
+    // workgroup id -> (row tile, split, b, h); the row tile is the slowest index
     const int m_tiles = (p.Lq + kBM - 1) / kBM;
-    const int mt_raw = blockIdx.x % m_tiles;
-    const int sp = blockIdx.x / m_tiles;
-    const int mt = p.causal ? m_tiles - 1 - mt_raw : mt_raw;      // longest rows first
-    const int h = blockIdx.y;
-    const int b = blockIdx.z;
+    const int n_bh = p.B * p.Hq;
+    const int per_rank = n_bh * p.splits;
+    const int mt_rank = blockIdx.x / per_rank;
+    const int rem = blockIdx.x % per_rank;
+    const int sp = rem / n_bh;
+    const int bh = rem % n_bh;
+    const int b = bh / p.Hq;
+    const int h = bh % p.Hq;
+    const int mt = p.causal ? m_tiles - 1 - mt_rank : mt_rank;     // longest rows first
     const int kvh = h / (p.Hq / p.Hkv);
     const int m0 = mt * kBM;
     const int wrow0 = m0 + wave * 32;
@@ -67,15 +251,6 @@ void tile_kernel(Problem p) {
     const uint16_t* vg = static_cast<const uint16_t*>(p.v) +
                          ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
 
-    // Q fragments: B operand of S^T = K Q^T, kept for the whole kernel
-    uint4 qf[NKK];
-    {
-        const int qr = min(my_row, p.Lq - 1);
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
-            qf[kk] = *reinterpret_cast<const uint4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
-    }
-
     const int nvis = visible_count(p, my_row);
     const bool wave_live = wrow0 < p.Lq;
     const int wave_nvis_max = wave_live ? visible_count(p, min(wrow0 + 31, p.Lq - 1)) : 0;
@@ -86,131 +261,83 @@ void tile_kernel(Problem p) {
     const int t_begin = sp * per_split;
     const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
 
-    const float c_log2 = p.scale * kLog2e;        // scores are carried in log2 units
-    const float ninf = -__builtin_inff();
+    if (t_begin < t_end) tile_dma<D>(kg, vg, t_begin * kBC, p.Lk, wave, lane, k0s, v0s);
 
-    f32x16 U[NDB];
+    TileRegs<D> g;
+    {
+        // Q fragments: B operand of S^T = K Q^T, kept for the whole kernel
+        const int qr = min(my_row, p.Lq - 1);
 #pragma unroll
-    for (int i = 0; i < NDB; ++i)
+        for (int kk = 0; kk < NKK; ++kk)
+            g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
+        // operand addresses inside a tile (elements)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) U[i][r] = 0.0f;
-    float lam = ninf;      // FLASH-D: Lam in log2 units.  ONLINE: running max m.
-    float beta = 1.0f;     // FLASH-D: factor still owed to U.  ONLINE: running sum l.
-    if (ONLINE) beta = 0.0f;
-
-    for (int kt = t_begin; kt < t_end; ++kt) {
-        const int j0 = kt * kBC;
-        __syncthreads();
-        // ---- K tile: 16-byte chunks, row-major, padded rows
+        for (int kk = 0; kk < NKK; ++kk)
+            g.kaddr[kk] = col * D + 8 * ((2 * kk + hh) ^ C::swz_k(col));
+        const int t = lane & 15;
+        const int tq = t >> 2;
+        const int half = (lane >> 4) & 1;
 #pragma unroll
-        for (int n = 0; n < (kBC * D / 8) / kTileThreads; ++n) {
-            const int c = tid + n * kTileThreads;
-            const int key = c / (D / 8);
-            const int part = c % (D / 8);
-            const int jr = min(j0 + key, p.Lk - 1);
-            const uint4 x = *reinterpret_cast<const uint4*>(kg + (size_t)jr * D + 8 * part);
-            *reinterpret_cast<uint4*>(&ks[key * KROW + 8 * part]) = x;
-        }
-        // ---- V tile: 4x4 blocks transposed in registers, keys permuted inside each
-        // 16-key group to the operand order (group position 8*(quad%2) + 4*(quad/2))
-#pragma unroll
-        for (int n = 0; n < (kBC / 4) * (D / 4) / kTileThreads; ++n) {
-            const int id = tid + n * kTileThreads;
-            const int dq = id % (D / 4);
-            const int kq = id / (D / 4);
-            uint32_t lo[4], hi[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int jr = min(j0 + 4 * kq + i, p.Lk - 1);
-                const uint2 x = *reinterpret_cast<const uint2*>(vg + (size_t)jr * D + 4 * dq);
-                lo[i] = x.x;
-                hi[i] = x.y;
-            }
-            const int quad = kq & 3;
-            const int pos = 16 * (kq >> 2) + 8 * (quad & 1) + 4 * (quad >> 1);
-            uint2 c0, c1, c2, c3;
-            c0.x = __builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u);
-            c0.y = __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u);
-            c1.x = __builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u);
-            c1.y = __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u);
-            c2.x = __builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u);
-            c2.y = __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u);
-            c3.x = __builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u);
-            c3.y = __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u);
-            *reinterpret_cast<uint2*>(&vt[(4 * dq + 0) * VROW + pos]) = c0;
-            *reinterpret_cast<uint2*>(&vt[(4 * dq + 1) * VROW + pos]) = c1;
-            *reinterpret_cast<uint2*>(&vt[(4 * dq + 2) * VROW + pos]) = c2;
-            *reinterpret_cast<uint2*>(&vt[(4 * dq + 3) * VROW + pos]) = c3;
-        }
-        __syncthreads();
-        if (j0 >= wave_nvis_max) continue;       // nothing visible to this wavefront
-
-        // ---- S^T = K Q^T for the two 32-key blocks
-        f32x16 acc[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
-#pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) {
-                const uint4 a = *reinterpret_cast<const uint4*>(
-                    &ks[(32 * kb + col) * KROW + 16 * kk + 8 * hh]);
-                acc[kb] = Mma<T>::mfma(a, qf[kk], acc[kb]);
-            }
-        }
-        // ---- scale to log2 units; masked keys get -inf (not an iteration)
-        const bool need_mask = j0 + kBC > wave_nvis_min;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = acc[kb][r] * c_log2;
-                if (need_mask) {
-                    const int j = j0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (j >= nvis) s = ninf;
-                }
-                acc[kb][r] = s;
-            }
-
-        // ---- per-row state update; acc becomes the coefficients p_j
-        const float f = row_step<T, 2, ONLINE>(acc, lam, beta);
-
-        // ---- U <- f U + P V   (O^T = V^T P^T)
+        for (int i = 0; i < NDB; ++i)
+            g.vaddr[i] = (4 * hh + tq) * D +
+                         8 * ((4 * i + 2 * half + ((t & 3) >> 1)) ^ C::swz_v(tq)) + 4 * (t & 1);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) U[i][r] *= f;
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            f32x8 pv;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pv[e] = acc[g4 >> 1][8 * (g4 & 1) + e];
-            const uint4 bfrag = Mma<T>::pack8(pv);
-#pragma unroll
-            for (int i = 0; i < NDB; ++i) {
-                const uint4 a = *reinterpret_cast<const uint4*>(
-                    &vt[(32 * i + col) * VROW + 16 * g4 + 8 * hh]);
-                U[i] = Mma<T>::mfma(a, bfrag, U[i]);
-            }
+            for (int r = 0; r < 16; ++r) g.U[i][r] = 0.0f;
+        g.st = {0.0f, 1.0f, 0.0f};
+        g.lam = -__builtin_inff();
+        g.beta = 0.0f;
+    }
+
+    const float c_log2 = p.scale * kLog2e;        // scores are carried in log2 units
+    const float ninf = -__builtin_inff();
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // two tiles per trip so that each half works on fixed buffers
+    for (int kt = t_begin; kt < t_end; kt += 2) {
+        {
+            const int j0 = kt * kBC;
+            if (kt + 1 < t_end) tile_dma<D>(kg, vg, j0 + kBC, p.Lk, wave, lane, k1s, v1s);
+            if (j0 < wave_nvis_max)
+                tile_compute<T, D, ONLINE>(k0s, v0s, g, j0, hh, lane, nvis,
+                                           j0 + kBC > wave_nvis_min, c_log2);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+        if (kt + 1 < t_end) {
+            const int j0 = (kt + 1) * kBC;
+            if (kt + 2 < t_end) tile_dma<D>(kg, vg, j0 + kBC, p.Lk, wave, lane, k0s, v0s);
+            if (j0 < wave_nvis_max)
+                tile_compute<T, D, ONLINE>(k1s, v1s, g, j0, hh, lane, nvis,
+                                           j0 + kBC > wave_nvis_min, c_log2);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
         }
     }
 
     if (my_row >= p.Lq) return;
-    // ---- epilogue.  FLASH-D: the output is the state (times the factor still owed);
-    // ONLINE: the one division of Alg. 2.
+    // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
     float fin, lam_out;
-    row_finish<ONLINE>(lam, beta, fin, lam_out);
+    if (!ONLINE) {
+        fin = g.st.beta;
+        lam_out = g.st.one == 0.0f ? ninf : g.st.R - log2_fast(g.st.beta);
+    } else {
+        row_finish<true>(g.lam, g.beta, fin, lam_out);
+    }
     if (p.splits == 1) {
         uint16_t* og = static_cast<uint16_t*>(p.o) +
                        (((size_t)b * p.Hq + h) * (size_t)p.Lq + my_row) * D;
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int dc = 32 * i + 8 * g + 4 * hh;
+            for (int gq = 0; gq < 4; ++gq) {
+                const int dc = 32 * i + 8 * gq + 4 * hh;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    Store<T>::store(og, dc + e, U[i][4 * g + e] * fin);
+                    Store<T>::store(og, dc + e, g.U[i][4 * gq + e] * fin);
             }
     } else {
         // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
@@ -219,11 +346,11 @@ void tile_kernel(Problem p) {
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int dc = 32 * i + 8 * g + 4 * hh;
+            for (int gq = 0; gq < 4; ++gq) {
+                const int dc = 32 * i + 8 * gq + 4 * hh;
                 float4 x;
-                x.x = U[i][4 * g + 0] * fin; x.y = U[i][4 * g + 1] * fin;
-                x.z = U[i][4 * g + 2] * fin; x.w = U[i][4 * g + 3] * fin;
+                x.x = g.U[i][4 * gq + 0] * fin; x.y = g.U[i][4 * gq + 1] * fin;
+                x.z = g.U[i][4 * gq + 2] * fin; x.w = g.U[i][4 * gq + 3] * fin;
                 *reinterpret_cast<float4*>(dst + dc) = x;
             }
         if (hh == 0) { dst[D] = lam_out * kLn2; dst[D + 1] = 0.0f; }
@@ -232,8 +359,10 @@ void tile_kernel(Problem p) {
 
 template <typename T, int D>
 static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
-    const int m_tiles = (p.Lq + kBM - 1) / kBM;
-    dim3 grid((unsigned)(m_tiles * p.splits), (unsigned)p.Hq, (unsigned)p.B);
+    const long m_tiles = (p.Lq + kBM - 1) / kBM;
+    const long total = m_tiles * p.splits * p.B * p.Hq;
+    if (total > 0x7fffffffL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)total);
     if (online)
         hipLaunchKernelGGL((tile_kernel<T, D, true>), grid, dim3(kTileThreads), 0, st, p);
     else
