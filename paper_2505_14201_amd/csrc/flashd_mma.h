@@ -202,7 +202,8 @@ template <> struct LazyLimit<F16> { static constexpr float kMaxPsum = 16384.0f; 
 // row is risky; in that case the state is left untouched.
 template <typename T, int NB>
 __device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float c_log2,
-                                          bool need_mask, int jb, int nvis, int lane) {
+                                          bool need_mask, int jb, int nvis, int lane,
+                                          float& ref_used) {
     const float ninf = -__builtin_inff();
     const bool empty = st.one == 0.0f;
     float ref = st.R;
@@ -224,6 +225,7 @@ __device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float 
             acc[kb][r] = pj;
         }
     psum += __shfl_xor(psum, 32, 64);
+    ref_used = ref;
     const bool risky = !(psum <= LazyLimit<T>::kMaxPsum);
     if (!risky && !(empty && psum == 0.0f)) {
         const float tot = fmaf(st.beta, psum, st.one);
@@ -239,7 +241,8 @@ __device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float 
 //   lazy_chain_block  folds one block's visible scores into the lane's run Lam (ll)
 //   lazy_new_state    folds partner lane and carried state, updates risky rows' state and
 //                     returns the new reference and the factor for U (1 for other rows)
-//   lazy_apply_block  replaces the p_j of risky rows by c_j = 2^{s_j - Lam_new} <= 1
+//   lazy_apply_block  recomputes one block's p_j = 2^{s_j - ref}; risky rows pass ref =
+//                     Lam_new, so their c_j <= 1
 // Key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j - Lam_{j-1}), i.e.
 // w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the first visible key
 // starts the run (w = 1).  The sigmoid saturates, whatever the jump.
@@ -271,10 +274,9 @@ __device__ __forceinline__ float lazy_new_state(LazyRow& st, bool risky, float l
     return f;
 }
 
-__device__ __forceinline__ void lazy_apply_block(f32x16& acc, const f32x16& raw, bool risky,
-                                                 float ref, float c_log2, bool need_mask,
-                                                 int jb_blk, int nvis, bool none) {
-    if (!risky) return;
+__device__ __forceinline__ void lazy_apply_block(f32x16& acc, const f32x16& raw, float ref,
+                                                 float c_log2, bool need_mask, int jb_blk,
+                                                 int nvis, bool none) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         float x = fmaf(raw[r], c_log2, -ref);

@@ -63,14 +63,48 @@ template <> struct TileCfg<64> {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Start the direct global->LDS copy of the K and V tiles whose first key is j0.  Every
-// wavefront issues CPR/4 instructions per tensor, each moving 64 chunks of 16 bytes to 1 KB
-// of LDS.  Keys past the end are clamped to the last key (masked later).
+// Per-lane element offsets of the direct global->LDS copy.  Instruction n of a wavefront
+// (n < CPR/4) moves 64 chunks of 16 bytes into 1 KB of LDS: lane l fills chunk position
+// cs = l % CPR of tile row 16*wave + n*(64/CPR) + l/CPR.  With the swizzles above the
+// global chunk to fetch is cs ^ (l >> 4) ^ 4n for K and cs ^ swz_v for V (independent of
+// n), so the offsets are (k0 ^ 32n) + 512n and v0 + 512n elements.
+template <int D> struct DmaLane {
+    int k0, v0;
+    __device__ __forceinline__ DmaLane(int wave, int lane) {
+        using C = TileCfg<D>;
+        const int row = 16 * wave + lane / C::CPR;
+        const int cs = lane % C::CPR;
+        k0 = row * D + 8 * (cs ^ (lane >> 4));
+        v0 = row * D + 8 * (cs ^ C::swz_v(row));
+    }
+};
+
+// Start the copy of the K and V tiles whose first key is j0 (all 64 keys in range).
 template <int D>
-__device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
-                                         int wave, int lane, uint16_t* ks, uint16_t* vs) {
+__device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg, int j0,
+                                         const DmaLane<D>& dl, int wave, uint16_t* ks,
+                                         uint16_t* vs) {
     using C = TileCfg<D>;
+    const uint16_t* kt = kg + (size_t)j0 * D;       // wavefront-uniform tile bases
+    const uint16_t* vt = vg + (size_t)j0 * D;
 #pragma unroll
+    for (int n = 0; n < C::CPR / 4; ++n) {
+        const int inst = wave * (C::CPR / 4) + n;
+        __builtin_amdgcn_global_load_lds((gptr_t)(kt + ((dl.k0 ^ (32 * n)) + 512 * n)),
+                                         (lptr_t)(ks + inst * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(vt + (dl.v0 + 512 * n)),
+                                         (lptr_t)(vs + inst * 512), 16, 0, 0);
+    }
+}
+
+// The same for a tile that sticks out past the last key: rows are clamped to the last
+// key (their scores are masked later).
+template <int D>
+__device__ __forceinline__ void tile_dma_tail(const uint16_t* kg, const uint16_t* vg, int j0,
+                                              int Lk, int wave, int lane, uint16_t* ks,
+                                              uint16_t* vs) {
+    using C = TileCfg<D>;
+#pragma unroll 1
     for (int n = 0; n < C::CPR / 4; ++n) {
         const int inst = wave * (C::CPR / 4) + n;
         const int slot = inst * 64 + lane;
@@ -82,6 +116,14 @@ __device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg,
         __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
                                          (lptr_t)(vs + inst * 512), 16, 0, 0);
     }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
+                                          const DmaLane<D>& dl, int wave, int lane, uint16_t* ks,
+                                          uint16_t* vs) {
+    if (j0 + kBC <= Lk) tile_dma<D>(kg, vg, j0, dl, wave, ks, vs);
+    else tile_dma_tail<D>(kg, vg, j0, Lk, wave, lane, ks, vs);
 }
 
 // raw S^T = K Q^T for one 32-key block of a tile; kaddr[kk] = this lane's element offset
@@ -146,14 +188,50 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
                                              bool need_mask, float c_log2) {
     constexpr int NDB = D / 32;
     const float ninf = -__builtin_inff();
+    // Operand reads run kAhead products ahead of the matrix instructions that consume them
+    // (LDS returns in order), and V's first operands are requested before the per-row
+    // arithmetic so that their latency hides behind it.
+    constexpr int NK = 2 * (D / 16);      // K operands / score products per tile
+    constexpr int NV = 4 * NDB;           // V operands / output products per tile
+    constexpr int kAhead = 8;
     f32x16 acc[2];
-    tile_scores<T, D>(ks, g.qf, g.kaddr, acc);
+    {
+        u32x4 ka[NK];
+#pragma unroll
+        for (int m = 0; m < kAhead; ++m)
+            ka[m] = *reinterpret_cast<const u32x4*>(&ks[g.kaddr[m >> 1] + 32 * D * (m & 1)]);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
+#pragma unroll
+        for (int m = 0; m < NK; ++m) {
+            acc[m & 1] = Mma<T>::mfma(ka[m], g.qf[m >> 1], acc[m & 1]);
+            if (m + kAhead < NK)
+                ka[m + kAhead] = *reinterpret_cast<const u32x4*>(
+                    &ks[g.kaddr[(m + kAhead) >> 1] + 32 * D * ((m + kAhead) & 1)]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+        for (int m = 0; m < NK - kAhead; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 va[NV];
+#pragma unroll
+    for (int m = 0; m < kAhead; ++m)
+        va[m] = tile_v_operand<D>(vs, g.vaddr[m % NDB], 16 * (m / NDB));
+    __builtin_amdgcn_sched_barrier(0);
     const int jb = j0 + 4 * hh;
 
     if (!ONLINE) {
-        const bool risky = lazy_spec<T, 2>(acc, g.st, c_log2, need_mask, jb, nvis, lane);
+        float ref;
+        const bool risky = lazy_spec<T, 2>(acc, g.st, c_log2, need_mask, jb, nvis, lane, ref);
         if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // rare: redo the tile for the flagged rows from recomputed raw scores
+            // rare: redo the tile from recomputed raw scores, one 32-key block at a time
             f32x16 raw;
             float ll = ninf;
 #pragma unroll 1
@@ -161,18 +239,14 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
                 tile_scores_block<T, D>(ks, g.qf, g.kaddr, kb, raw);
                 lazy_chain_block(raw, ll, c_log2, need_mask, jb + 32 * kb, nvis);
             }
-            float ref;
-            const float f = lazy_new_state(g.st, risky, ll, ref);
+            float ref_new;
+            const float f = lazy_new_state(g.st, risky, ll, ref_new);
             const bool none = risky && g.st.one == 0.0f;
-#pragma unroll 1
-            for (int kb = 0; kb < 2; ++kb) {
-                tile_scores_block<T, D>(ks, g.qf, g.kaddr, kb, raw);
-                if (kb == 0)
-                    lazy_apply_block(acc[0], raw, risky, ref, c_log2, need_mask, jb, nvis, none);
-                else
-                    lazy_apply_block(acc[1], raw, risky, ref, c_log2, need_mask, jb + 32, nvis,
-                                     none);
-            }
+            if (risky) ref = ref_new;
+            tile_scores_block<T, D>(ks, g.qf, g.kaddr, 0, raw);
+            lazy_apply_block(acc[0], raw, ref, c_log2, need_mask, jb, nvis, none);
+            tile_scores_block<T, D>(ks, g.qf, g.kaddr, 1, raw);
+            lazy_apply_block(acc[1], raw, ref, c_log2, need_mask, jb + 32, nvis, none);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -195,17 +269,29 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
     }
 
     // ---- U <- U + P V   (O^T = V^T P^T)
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 bfrag[4];
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
         f32x8 pv;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pv[e] = acc[g4 >> 1][8 * (g4 & 1) + e];
-        const u32x4 bfrag = Mma<T>::pack8(pv);
+        bfrag[g4] = Mma<T>::pack8(pv);
+    }
 #pragma unroll
-        for (int i = 0; i < NDB; ++i) {
-            const u32x4 a = tile_v_operand<D>(vs, g.vaddr[i], 16 * g4);
-            g.U[i] = Mma<T>::mfma(a, bfrag, g.U[i]);
+    for (int m = 0; m < NV; ++m) {
+        g.U[m % NDB] = Mma<T>::mfma(va[m], bfrag[m / NDB], g.U[m % NDB]);
+        if (m + kAhead < NV)
+            va[m + kAhead] =
+                tile_v_operand<D>(vs, g.vaddr[(m + kAhead) % NDB], 16 * ((m + kAhead) / NDB));
+    }
+    if (NV > kAhead) {
+#pragma unroll
+        for (int m = 0; m < NV - kAhead; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     }
 }
 
@@ -215,16 +301,16 @@ void tile_kernel(Problem p) {
     using C = TileCfg<D>;
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
-    // two buffers, as separate objects so that LDS reads of one need not wait for the
-    // asynchronous copy into the other
-    __shared__ __align__(1024) uint16_t k0s[kBC * D];
-    __shared__ __align__(1024) uint16_t v0s[kBC * D];
-    __shared__ __align__(1024) uint16_t k1s[kBC * D];
-    __shared__ __align__(1024) uint16_t v1s[kBC * D];
+    // two buffers of a K tile and a V tile each
+    __shared__ __align__(1024) uint16_t lds[4 * kBC * D];
+    uint16_t* const k0s = lds;
+    uint16_t* const v0s = lds + kBC * D;
+    uint16_t* const k1s = lds + 2 * kBC * D;
+    uint16_t* const v1s = lds + 3 * kBC * D;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront-uniform
     const int col = lane & 31;
     const int hh = lane >> 5;
 
@@ -261,7 +347,8 @@ void tile_kernel(Problem p) {
     const int t_begin = sp * per_split;
     const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
 
-    if (t_begin < t_end) tile_dma<D>(kg, vg, t_begin * kBC, p.Lk, wave, lane, k0s, v0s);
+    const DmaLane<D> dl(wave, lane);
+    if (t_begin < t_end) tile_copy<D>(kg, vg, t_begin * kBC, p.Lk, dl, wave, lane, k0s, v0s);
 
     TileRegs<D> g;
     {
@@ -300,7 +387,7 @@ void tile_kernel(Problem p) {
     for (int kt = t_begin; kt < t_end; kt += 2) {
         {
             const int j0 = kt * kBC;
-            if (kt + 1 < t_end) tile_dma<D>(kg, vg, j0 + kBC, p.Lk, wave, lane, k1s, v1s);
+            if (kt + 1 < t_end) tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k1s, v1s);
             if (j0 < wave_nvis_max)
                 tile_compute<T, D, ONLINE>(k0s, v0s, g, j0, hh, lane, nvis,
                                            j0 + kBC > wave_nvis_min, c_log2);
@@ -309,7 +396,7 @@ void tile_kernel(Problem p) {
         }
         if (kt + 1 < t_end) {
             const int j0 = (kt + 1) * kBC;
-            if (kt + 2 < t_end) tile_dma<D>(kg, vg, j0 + kBC, p.Lk, wave, lane, k0s, v0s);
+            if (kt + 2 < t_end) tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k0s, v0s);
             if (j0 < wave_nvis_max)
                 tile_compute<T, D, ONLINE>(k1s, v1s, g, j0, hh, lane, nvis,
                                            j0 + kBC > wave_nvis_min, c_log2);
