@@ -200,10 +200,10 @@ template <> struct LazyLimit<F16> { static constexpr float kMaxPsum = 16384.0f; 
 // acc: raw dot products in the accumulator layout -> coefficients p_j.  jb = index of the
 // key held in register 0 of block 0 by this lane (tile start + 4 hh).  Returns true if the
 // row is risky; in that case the state is left untouched.
-template <typename T, int NB>
-__device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float c_log2,
-                                          bool need_mask, int jb, int nvis, int lane,
-                                          float& ref_used) {
+// MASK = false: every key of the tile is visible to every row of the wavefront (no compare).
+template <typename T, int NB, bool MASK>
+__device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float c_log2, int jb,
+                                          int nvis, int lane, float& ref_used) {
     const float ninf = -__builtin_inff();
     const bool empty = st.one == 0.0f;
     float ref = st.R;
@@ -219,7 +219,7 @@ __device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float x = fmaf(acc[kb][r], c_log2, -ref);
-            if (need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
+            if (MASK && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
             const float pj = exp2_fast(x);
             psum += pj;
             acc[kb][r] = pj;

@@ -36,6 +36,8 @@
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
 
+#include <type_traits>
+
 namespace flashd {
 
 constexpr int kBM = 128;          // query rows per workgroup
@@ -229,7 +231,9 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
 
     if (!ONLINE) {
         float ref;
-        const bool risky = lazy_spec<T, 2>(acc, g.st, c_log2, need_mask, jb, nvis, lane, ref);
+        bool risky;
+        if (need_mask) risky = lazy_spec<T, 2, true>(acc, g.st, c_log2, jb, nvis, lane, ref);
+        else risky = lazy_spec<T, 2, false>(acc, g.st, c_log2, jb, nvis, lane, ref);
         if (__builtin_amdgcn_ballot_w64(risky) != 0) {
             // rare: redo the tile from recomputed raw scores, one 32-key block at a time
             f32x16 raw;
@@ -253,14 +257,21 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
                 for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
         }
     } else {
+        if (need_mask) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = acc[kb][r] * c_log2;
-                if (need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
-                acc[kb][r] = s;
-            }
+                for (int r = 0; r < 16; ++r) {
+                    float s = acc[kb][r] * c_log2;
+                    if ((jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
+                    acc[kb][r] = s;
+                }
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[kb][r] *= c_log2;
+        }
         const float f = row_step<T, 2, true>(acc, g.lam, g.beta);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
@@ -405,7 +416,6 @@ void tile_kernel(Problem p) {
         }
     }
 
-    if (my_row >= p.Lq) return;
     // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
     float fin, lam_out;
     if (!ONLINE) {
@@ -415,18 +425,47 @@ void tile_kernel(Problem p) {
         row_finish<true>(g.lam, g.beta, fin, lam_out);
     }
     if (p.splits == 1) {
-        uint16_t* og = static_cast<uint16_t*>(p.o) +
-                       (((size_t)b * p.Hq + h) * (size_t)p.Lq + my_row) * D;
+        // Stage the wavefront's 32 x D output block through LDS (the tile buffers are idle
+        // after the last barrier; each wavefront uses its own 32 * D elements) so that the
+        // global stores are 16 bytes per lane and whole rows are contiguous.  Chunk c of
+        // row r sits at chunk position c ^ (r % CPR) to keep the 8-byte writes and the
+        // 16-byte reads off each other's banks.
+        uint16_t* stage = lds + wave * (32 * D);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                const int dc = 32 * i + 8 * gq + 4 * hh;
+                const int dc = 32 * i + 8 * gq + 4 * hh;            // 4 consecutive columns
+                uint16_t h4[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    Store<T>::store(og, dc + e, g.U[i][4 * gq + e] * fin);
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (std::is_same<T, BF16>::value)
+                        h4[e] = f32_to_bf16(g.U[i][4 * gq + e] * fin);
+                    else
+                        h4[e] = __builtin_bit_cast(uint16_t,
+                                                   static_cast<_Float16>(g.U[i][4 * gq + e] * fin));
+                }
+                const int chunk = (dc >> 3) ^ (col % C::CPR);
+                u32x2 w2;
+                w2[0] = (uint32_t)h4[0] | ((uint32_t)h4[1] << 16);
+                w2[1] = (uint32_t)h4[2] | ((uint32_t)h4[3] << 16);
+                *reinterpret_cast<u32x2*>(&stage[col * D + 8 * chunk + (dc & 4)]) = w2;
             }
-    } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint16_t* og = static_cast<uint16_t*>(p.o) + ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
+#pragma unroll
+        for (int n = 0; n < 32 * C::CPR / 64; ++n) {
+            const int slot = n * 64 + lane;
+            const int r = slot / C::CPR;
+            const int c = slot % C::CPR;
+            const u32x4 x =
+                *reinterpret_cast<const u32x4*>(&stage[r * D + 8 * (c ^ (r % C::CPR))]);
+            if (wrow0 + r < p.Lq)
+                *reinterpret_cast<u32x4*>(og + (size_t)(wrow0 + r) * D + 8 * c) = x;
+        }
+    } else if (my_row < p.Lq) {
         // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
         float* dst = p.ws +
                      ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + my_row) * (D + 2);
