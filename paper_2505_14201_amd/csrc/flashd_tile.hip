@@ -36,13 +36,12 @@
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace flashd {
 
-constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kBC = 64;           // keys per tile
-constexpr int kTileThreads = 256;
 
 // LDS layout of one K or V tile: [64 keys][D] elements, rows unpadded (the direct
 // global->LDS loads write 64 consecutive 16-byte chunks per instruction, so rows cannot
@@ -66,32 +65,32 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // Per-lane element offsets of the direct global->LDS copy.  Instruction n of a wavefront
-// (n < CPR/4) moves 64 chunks of 16 bytes into 1 KB of LDS: lane l fills chunk position
-// cs = l % CPR of tile row 16*wave + n*(64/CPR) + l/CPR.  With the swizzles above the
+// (n < CPR/NW, NW wavefronts) moves 64 chunks of 16 bytes into 1 KB of LDS: lane l fills
+// chunk position cs = l % CPR of tile row (64/NW)*wave + n*(64/CPR) + l/CPR.  With the swizzles above the
 // global chunk to fetch is cs ^ (l >> 4) ^ 4n for K and cs ^ swz_v for V (independent of
 // n), so the offsets are (k0 ^ 32n) + 512n and v0 + 512n elements.
-template <int D> struct DmaLane {
+template <int D, int NW> struct DmaLane {
     int k0, v0;
     __device__ __forceinline__ DmaLane(int wave, int lane) {
         using C = TileCfg<D>;
-        const int row = 16 * wave + lane / C::CPR;
+        const int row = (kBC / NW) * wave + lane / C::CPR;     // row of this lane for n = 0
         const int cs = lane % C::CPR;
-        k0 = row * D + 8 * (cs ^ (lane >> 4));
+        k0 = row * D + 8 * (cs ^ C::swz_k(row));
         v0 = row * D + 8 * (cs ^ C::swz_v(row));
     }
 };
 
 // Start the copy of the K and V tiles whose first key is j0 (all 64 keys in range).
-template <int D>
+template <int D, int NW>
 __device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg, int j0,
-                                         const DmaLane<D>& dl, int wave, uint16_t* ks,
+                                         const DmaLane<D, NW>& dl, int wave, uint16_t* ks,
                                          uint16_t* vs) {
     using C = TileCfg<D>;
     const uint16_t* kt = kg + (size_t)j0 * D;       // wavefront-uniform tile bases
     const uint16_t* vt = vg + (size_t)j0 * D;
 #pragma unroll
-    for (int n = 0; n < C::CPR / 4; ++n) {
-        const int inst = wave * (C::CPR / 4) + n;
+    for (int n = 0; n < C::CPR / NW; ++n) {
+        const int inst = wave * (C::CPR / NW) + n;
         __builtin_amdgcn_global_load_lds((gptr_t)(kt + ((dl.k0 ^ (32 * n)) + 512 * n)),
                                          (lptr_t)(ks + inst * 512), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((gptr_t)(vt + (dl.v0 + 512 * n)),
@@ -101,14 +100,14 @@ __device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg,
 
 // The same for a tile that sticks out past the last key: rows are clamped to the last
 // key (their scores are masked later).
-template <int D>
+template <int D, int NW>
 __device__ __forceinline__ void tile_dma_tail(const uint16_t* kg, const uint16_t* vg, int j0,
                                               int Lk, int wave, int lane, uint16_t* ks,
                                               uint16_t* vs) {
     using C = TileCfg<D>;
 #pragma unroll 1
-    for (int n = 0; n < C::CPR / 4; ++n) {
-        const int inst = wave * (C::CPR / 4) + n;
+    for (int n = 0; n < C::CPR / NW; ++n) {
+        const int inst = wave * (C::CPR / NW) + n;
         const int slot = inst * 64 + lane;
         const int row = slot / C::CPR;
         const int cs = slot % C::CPR;
@@ -120,12 +119,12 @@ __device__ __forceinline__ void tile_dma_tail(const uint16_t* kg, const uint16_t
     }
 }
 
-template <int D>
+template <int D, int NW>
 __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
-                                          const DmaLane<D>& dl, int wave, int lane, uint16_t* ks,
-                                          uint16_t* vs) {
-    if (j0 + kBC <= Lk) tile_dma<D>(kg, vg, j0, dl, wave, ks, vs);
-    else tile_dma_tail<D>(kg, vg, j0, Lk, wave, lane, ks, vs);
+                                          const DmaLane<D, NW>& dl, int wave, int lane,
+                                          uint16_t* ks, uint16_t* vs) {
+    if (j0 + kBC <= Lk) tile_dma<D, NW>(kg, vg, j0, dl, wave, ks, vs);
+    else tile_dma_tail<D, NW>(kg, vg, j0, Lk, wave, lane, ks, vs);
 }
 
 // raw S^T = K Q^T for one 32-key block of a tile; kaddr[kk] = this lane's element offset
@@ -306,10 +305,13 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
     }
 }
 
-template <typename T, int D, bool ONLINE>
-__global__ __launch_bounds__(kTileThreads, 2)
+// NW wavefronts of 32 query rows each per workgroup; two wavefronts per SIMD either way
+// (NW = 4: two workgroups per compute unit, NW = 8: one).
+template <typename T, int D, bool ONLINE, int NW>
+__global__ __launch_bounds__(NW * 64, 8 / NW)
 void tile_kernel(Problem p) {
     using C = TileCfg<D>;
+    constexpr int kBM = 32 * NW;      // query rows per workgroup
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
     // two buffers of a K tile and a V tile each
@@ -358,8 +360,8 @@ void tile_kernel(Problem p) {
     const int t_begin = sp * per_split;
     const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
 
-    const DmaLane<D> dl(wave, lane);
-    if (t_begin < t_end) tile_copy<D>(kg, vg, t_begin * kBC, p.Lk, dl, wave, lane, k0s, v0s);
+    const DmaLane<D, NW> dl(wave, lane);
+    if (t_begin < t_end) tile_copy<D, NW>(kg, vg, t_begin * kBC, p.Lk, dl, wave, lane, k0s, v0s);
 
     TileRegs<D> g;
     {
@@ -398,7 +400,7 @@ void tile_kernel(Problem p) {
     for (int kt = t_begin; kt < t_end; kt += 2) {
         {
             const int j0 = kt * kBC;
-            if (kt + 1 < t_end) tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k1s, v1s);
+            if (kt + 1 < t_end) tile_copy<D, NW>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k1s, v1s);
             if (j0 < wave_nvis_max)
                 tile_compute<T, D, ONLINE>(k0s, v0s, g, j0, hh, lane, nvis,
                                            j0 + kBC > wave_nvis_min, c_log2);
@@ -407,7 +409,7 @@ void tile_kernel(Problem p) {
         }
         if (kt + 1 < t_end) {
             const int j0 = (kt + 1) * kBC;
-            if (kt + 2 < t_end) tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k0s, v0s);
+            if (kt + 2 < t_end) tile_copy<D, NW>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k0s, v0s);
             if (j0 < wave_nvis_max)
                 tile_compute<T, D, ONLINE>(k1s, v1s, g, j0, hh, lane, nvis,
                                            j0 + kBC > wave_nvis_min, c_log2);
@@ -483,24 +485,42 @@ void tile_kernel(Problem p) {
     }
 }
 
-template <typename T, int D>
-static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
-    const long m_tiles = (p.Lq + kBM - 1) / kBM;
+template <typename T, int D, int NW>
+static hipError_t launch_tile_nw(const Problem& p, bool online, hipStream_t st) {
+    const long m_tiles = (p.Lq + 32 * NW - 1) / (32 * NW);
     const long total = m_tiles * p.splits * p.B * p.Hq;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     dim3 grid((unsigned)total);
     if (online)
-        hipLaunchKernelGGL((tile_kernel<T, D, true>), grid, dim3(kTileThreads), 0, st, p);
+        hipLaunchKernelGGL((tile_kernel<T, D, true, NW>), grid, dim3(NW * 64), 0, st, p);
     else
-        hipLaunchKernelGGL((tile_kernel<T, D, false>), grid, dim3(kTileThreads), 0, st, p);
+        hipLaunchKernelGGL((tile_kernel<T, D, false, NW>), grid, dim3(NW * 64), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_merge_splits(p, st);
 }
 
+// Rows per workgroup: 256 (8 wavefronts) halves the K/V traffic into LDS per unit of work
+// and pays off once there are enough 256-row tiles to fill the chip; 128 otherwise.
+static int tile_rows(int B, int Hq, int Lq) {
+    static const int forced = [] {
+        const char* e = getenv("FLASHD_TILE_ROWS");
+        return e ? atoi(e) : 0;
+    }();
+    if (forced == 128 || forced == 256) return forced;
+    return 128;
+}
+
+template <typename T, int D>
+static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
+    if (tile_rows(p.B, p.Hq, p.Lq) == 256) return launch_tile_nw<T, D, 8>(p, online, st);
+    return launch_tile_nw<T, D, 4>(p, online, st);
+}
+
 long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d) {
     (void)Hkv; (void)d;
-    return (long)B * Hq * ((Lq + kBM - 1) / kBM);
+    const int rows = tile_rows(B, Hq, Lq);
+    return (long)B * Hq * ((Lq + rows - 1) / rows);
 }
 
 hipError_t launch_tile(const Problem& p, bool online, hipStream_t st) {
