@@ -183,10 +183,11 @@ __device__ __forceinline__ float row_step(f32x16 (&acc)[NB], float& lam, float& 
 // (1 - W) folded into the scalar beta: U is never rescaled here.  An empty row takes the
 // score of the tile's first key as R (w_1 = 1 for that key).
 //
-// lazy_spec() does that speculatively and reports rows whose psum left the safe range
-// (some 2^{s_j - R} too large for the storage type: a score far above everything before
-// it).  For those rows lazy_rereference() redoes the tile from the raw scores with the
-// key-by-key sigmoid recurrence, which saturates instead of overflowing, and moves R.
+// lazy_spec_pack() does that speculatively, branch-free, leaving the raw scores untouched,
+// and reports rows whose psum left the safe range (some 2^{s_j - R} too large for the
+// storage type: a score far above everything before it).  For those rows lazy_redo_pack()
+// redoes the tile from the raw scores with the key-by-key sigmoid recurrence, which
+// saturates instead of overflowing, and moves R.
 struct LazyRow {
     float R;      // exponent reference, log2 units
     float beta;   // o = beta * U
@@ -197,93 +198,165 @@ template <typename T> struct LazyLimit;
 template <> struct LazyLimit<BF16> { static constexpr float kMaxPsum = 1.0e18f; };   // ~2^60
 template <> struct LazyLimit<F16> { static constexpr float kMaxPsum = 16384.0f; };   // each p_j < 2^14
 
-// acc: raw dot products in the accumulator layout -> coefficients p_j.  jb = index of the
-// key held in register 0 of block 0 by this lane (tile start + 4 hh).  Returns true if the
-// row is risky; in that case the state is left untouched.
-// MASK = false: every key of the tile is visible to every row of the wavefront (no compare).
-template <typename T, int NB, bool MASK>
-__device__ __forceinline__ bool lazy_spec(f32x16 (&acc)[NB], LazyRow& st, float c_log2, int jb,
-                                          int nvis, int lane, float& ref_used) {
+// x[lane] + x[lane ^ 32] without touching LDS: the swap returns {x_lo, x_lo} and {x_hi, x_hi}
+__device__ __forceinline__ float pair_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x),
+                                                    false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// the value held by the hh = 0 lane of the pair
+__device__ __forceinline__ float pair_low(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x),
+                                                    false, false);
+    return __uint_as_float(r[0]);
+}
+
+// acc: raw dot products of NB 32-key blocks in the accumulator layout (not modified).
+// bfrag[g]: the coefficients of 16-key group g, rounded to the storage type, as the B
+// operand of the output product.  jb = index of the key in register 0 of block 0 for this
+// lane (tile start + 4 hh).  MASK = false: every key is visible to every row of the
+// wavefront.  Returns true if the row is risky; its state is then left untouched.
+// MAY_BE_EMPTY = false promises that no row of the wavefront is still empty (true from a
+// row's second unit on); the code is then free of the first-key logic and stays one
+// basic block, which the caller needs to interleave it with matrix instructions.
+template <typename T, int NB, bool MASK, bool MAY_BE_EMPTY>
+__device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                               LazyRow& st, float c_log2, int jb, int nvis,
+                                               int lane) {
     const float ninf = -__builtin_inff();
-    const bool empty = st.one == 0.0f;
+    bool empty = false;
     float ref = st.R;
-    if (__builtin_amdgcn_ballot_w64(empty) != 0) {
+    if (MAY_BE_EMPTY) {
+        empty = st.one == 0.0f;
         // first key of the tile for this row: register 0 of block 0 in the hh = 0 lane
-        const float s0 = __shfl(acc[0][0], lane & 31, 64) * c_log2;
-        const bool vis0 = (jb - 4 * (lane >> 5)) < nvis;
-        if (empty) ref = vis0 ? s0 : 0.0f;
+        const float s0 = pair_low(acc[0][0]) * c_log2;
+        const float ref0 = ((jb - 4 * (lane >> 5)) < nvis) ? s0 : 0.0f;
+        ref = empty ? ref0 : st.R;
     }
     float psum = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+        f32x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = 8 * (g & 1) + e;
+            float x = fmaf(acc[g >> 1][r], c_log2, -ref);
+            if (MASK) x = ((jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis) ? ninf : x;
+            pv[e] = exp2_fast(x);
+            psum += pv[e];
+        }
+        bfrag[g] = Mma<T>::pack8(pv);
+    }
+    psum = pair_sum(psum);
+    const bool safe = psum <= LazyLimit<T>::kMaxPsum;             // false for inf and NaN
+    if (MAY_BE_EMPTY) {
+        const bool upd = safe & !(empty & (psum == 0.0f));
+        const float tot = fmaf(st.beta, psum, st.one);
+        const float nb = st.beta * __builtin_amdgcn_rcpf(tot);
+        st.beta = upd ? nb : st.beta;
+        st.R = upd ? ref : st.R;
+        st.one = upd ? 1.0f : st.one;
+    } else {
+        const float nb = st.beta * __builtin_amdgcn_rcpf(fmaf(st.beta, psum, 1.0f));
+        st.beta = safe ? nb : st.beta;
+    }
+    return !safe;
+}
+
+// Rare path, entered by the whole wavefront when any of its rows is risky.  Key-by-key
+// recurrence inside the lane over the raw scores: Lam_j = Lam_{j-1} + softplus(s_j -
+// Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the
+// first visible key starts the run (w = 1); the lane pair and the carried state are folded
+// by the same rule.  Risky rows get c_j = 2^{s_j - Lam_new} <= 1 and a new reference; the
+// other rows' coefficients are recomputed with the reference they used (same values; a
+// row that is still empty has every key masked, so its reference does not matter).
+// Returns the factor for the row's U (1 for rows that were not risky).
+template <typename T, int NB>
+__device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                                LazyRow& st, bool risky, float c_log2,
+                                                bool need_mask, int jb, int nvis) {
+    const float ninf = -__builtin_inff();
+    float ll = ninf;
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float x = fmaf(acc[kb][r], c_log2, -ref);
-            if (MASK && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
-            const float pj = exp2_fast(x);
-            psum += pj;
-            acc[kb][r] = pj;
+            const bool masked = need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis;
+            if (!masked) ll = lse2(ll, acc[kb][r] * c_log2);
         }
-    psum += __shfl_xor(psum, 32, 64);
-    ref_used = ref;
-    const bool risky = !(psum <= LazyLimit<T>::kMaxPsum);
-    if (!risky && !(empty && psum == 0.0f)) {
-        const float tot = fmaf(st.beta, psum, st.one);
-        st.beta *= __builtin_amdgcn_rcpf(tot);
-        st.R = ref;
-        st.one = 1.0f;
-    }
-    return risky;
-}
-
-// Re-reference, in three steps so that the caller can recompute the raw scores one 32-key
-// block at a time (acc already holds the speculative p_j):
-//   lazy_chain_block  folds one block's visible scores into the lane's run Lam (ll)
-//   lazy_new_state    folds partner lane and carried state, updates risky rows' state and
-//                     returns the new reference and the factor for U (1 for other rows)
-//   lazy_apply_block  recomputes one block's p_j = 2^{s_j - ref}; risky rows pass ref =
-//                     Lam_new, so their c_j <= 1
-// Key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j - Lam_{j-1}), i.e.
-// w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the first visible key
-// starts the run (w = 1).  The sigmoid saturates, whatever the jump.
-__device__ __forceinline__ void lazy_chain_block(const f32x16& raw, float& ll, float c_log2,
-                                                 bool need_mask, int jb_blk, int nvis) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const bool masked = need_mask && (jb_blk + 8 * (r >> 2) + (r & 3)) >= nvis;
-        if (!masked) ll = lse2(ll, raw[r] * c_log2);
-    }
-}
-
-__device__ __forceinline__ float lazy_new_state(LazyRow& st, bool risky, float ll, float& ref) {
-    const float ninf = -__builtin_inff();
     ll = lse2(ll, __shfl_xor(ll, 32, 64));                  // partner lane's run
     const bool empty = st.one == 0.0f;
     const float lam_old = empty ? ninf : st.R - log2_fast(st.beta);
     const float lam_new = lse2(lam_old, ll);                  // the tile acts as one key
-    const bool none = lam_new == ninf;
-    ref = none ? 0.0f : lam_new;
+    const bool none = risky && lam_new == ninf;
     float f = 1.0f;
+    float ref = st.R;     // rows that were not risky: the reference lazy_spec_pack used
     if (risky) {
+        ref = none ? 0.0f : lam_new;
         // the old state decays by 1 - W = 2^{Lam_old - Lam_new}; it is applied to U now
         f = empty ? 0.0f : st.beta * exp2_fast(lam_old - lam_new);
         st.beta = 1.0f;
         st.R = ref;
         st.one = none ? 0.0f : 1.0f;
     }
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+        f32x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = 8 * (g & 1) + e;
+            float x = fmaf(acc[g >> 1][r], c_log2, -ref);
+            const bool masked =
+                need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis;
+            if (masked || none) x = ninf;
+            pv[e] = exp2_fast(x);
+        }
+        bfrag[g] = Mma<T>::pack8(pv);
+    }
     return f;
 }
 
-__device__ __forceinline__ void lazy_apply_block(f32x16& acc, const f32x16& raw, float ref,
-                                                 float c_log2, bool need_mask, int jb_blk,
-                                                 int nvis, bool none) {
+// Alg. 2 on the same interface (ablation): m_i = max(m_{i-1}, s), l_i = l_{i-1}
+// e^{m_{i-1}-m_i} + sum e^{s-m_i}; returns the factor e^{m_{i-1}-m_i} for the row's U.
+template <typename T, int NB, bool MASK>
+__device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                             float& m, float& l, float c_log2, int jb, int nvis) {
+    const float ninf = -__builtin_inff();
+    float mx = ninf;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float x = fmaf(raw[r], c_log2, -ref);
-        const bool masked = need_mask && (jb_blk + 8 * (r >> 2) + (r & 3)) >= nvis;
-        if (masked || none) x = -__builtin_inff();
-        acc[r] = exp2_fast(x);
+    for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float s = acc[kb][r] * c_log2;
+            if (MASK && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
+            mx = fmaxf(mx, s);
+        }
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx),
+                                                         false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
     }
+    const float m_new = fmaxf(m, mx);
+    const float m_use = (m_new == ninf) ? 0.0f : m_new;
+    const float resc = exp2_fast(m - m_use);
+    float psum = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+        f32x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = 8 * (g & 1) + e;
+            float x = fmaf(acc[g >> 1][r], c_log2, -m_use);
+            if (MASK && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
+            pv[e] = exp2_fast(x);
+            psum += pv[e];
+        }
+        bfrag[g] = Mma<T>::pack8(pv);
+    }
+    psum = pair_sum(psum);
+    l = l * resc + psum;
+    m = m_new;
+    return resc;
 }
 
 // What a finished row hands on: the factor that turns U into the output, and the row's

@@ -80,82 +80,58 @@ template <int D, int NW> struct DmaLane {
     }
 };
 
-// Start the copy of the K and V tiles whose first key is j0 (all 64 keys in range).
+// Start the copy of the K (or V) tile whose first key is j0.  A tile that sticks out past
+// the last key takes the slow form with rows clamped to the last key (masked later).
 template <int D, int NW>
-__device__ __forceinline__ void tile_dma(const uint16_t* kg, const uint16_t* vg, int j0,
-                                         const DmaLane<D, NW>& dl, int wave, uint16_t* ks,
-                                         uint16_t* vs) {
+__device__ __forceinline__ void tile_copy_k(const uint16_t* kg, int j0, int Lk,
+                                            const DmaLane<D, NW>& dl, int wave, int lane,
+                                            uint16_t* ks) {
     using C = TileCfg<D>;
-    const uint16_t* kt = kg + (size_t)j0 * D;       // wavefront-uniform tile bases
-    const uint16_t* vt = vg + (size_t)j0 * D;
+    if (j0 + kBC <= Lk) {
+        const uint16_t* kt = kg + (size_t)j0 * D;       // wavefront-uniform tile base
 #pragma unroll
-    for (int n = 0; n < C::CPR / NW; ++n) {
-        const int inst = wave * (C::CPR / NW) + n;
-        __builtin_amdgcn_global_load_lds((gptr_t)(kt + ((dl.k0 ^ (32 * n)) + 512 * n)),
-                                         (lptr_t)(ks + inst * 512), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)(vt + (dl.v0 + 512 * n)),
-                                         (lptr_t)(vs + inst * 512), 16, 0, 0);
-    }
-}
-
-// The same for a tile that sticks out past the last key: rows are clamped to the last
-// key (their scores are masked later).
-template <int D, int NW>
-__device__ __forceinline__ void tile_dma_tail(const uint16_t* kg, const uint16_t* vg, int j0,
-                                              int Lk, int wave, int lane, uint16_t* ks,
-                                              uint16_t* vs) {
-    using C = TileCfg<D>;
+        for (int n = 0; n < C::CPR / NW; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(kt + ((dl.k0 ^ (32 * n)) + 512 * n)),
+                                             (lptr_t)(ks + (wave * (C::CPR / NW) + n) * 512), 16,
+                                             0, 0);
+    } else {
 #pragma unroll 1
-    for (int n = 0; n < C::CPR / NW; ++n) {
-        const int inst = wave * (C::CPR / NW) + n;
-        const int slot = inst * 64 + lane;
-        const int row = slot / C::CPR;
-        const int cs = slot % C::CPR;
-        const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
-        __builtin_amdgcn_global_load_lds((gptr_t)(kg + grow + 8 * (cs ^ C::swz_k(row))),
-                                         (lptr_t)(ks + inst * 512), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
-                                         (lptr_t)(vs + inst * 512), 16, 0, 0);
+        for (int n = 0; n < C::CPR / NW; ++n) {
+            const int inst = wave * (C::CPR / NW) + n;
+            const int slot = inst * 64 + lane;
+            const int row = slot / C::CPR;
+            const int cs = slot % C::CPR;
+            const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
+            __builtin_amdgcn_global_load_lds((gptr_t)(kg + grow + 8 * (cs ^ C::swz_k(row))),
+                                             (lptr_t)(ks + inst * 512), 16, 0, 0);
+        }
     }
 }
 
 template <int D, int NW>
-__device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
-                                          const DmaLane<D, NW>& dl, int wave, int lane,
-                                          uint16_t* ks, uint16_t* vs) {
-    if (j0 + kBC <= Lk) tile_dma<D, NW>(kg, vg, j0, dl, wave, ks, vs);
-    else tile_dma_tail<D, NW>(kg, vg, j0, Lk, wave, lane, ks, vs);
-}
-
-// raw S^T = K Q^T for one 32-key block of a tile; kaddr[kk] = this lane's element offset
-// of its kk-th operand chunk inside a K tile (block 0)
-template <typename T, int D>
-__device__ __forceinline__ void tile_scores_block(const uint16_t* ks, const u32x4 (&qf)[D / 16],
-                                                  const int (&kaddr)[D / 16], int kb, f32x16& acc) {
+__device__ __forceinline__ void tile_copy_v(const uint16_t* vg, int j0, int Lk,
+                                            const DmaLane<D, NW>& dl, int wave, int lane,
+                                            uint16_t* vs) {
+    using C = TileCfg<D>;
+    if (j0 + kBC <= Lk) {
+        const uint16_t* vt = vg + (size_t)j0 * D;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[kaddr[kk] + 32 * D * kb]);
-        acc = Mma<T>::mfma(a, qf[kk], acc);
-    }
-}
-
-// ... and for both blocks, the two accumulation chains interleaved
-template <typename T, int D>
-__device__ __forceinline__ void tile_scores(const uint16_t* ks, const u32x4 (&qf)[D / 16],
-                                            const int (&kaddr)[D / 16], f32x16 (&acc)[2]) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[kaddr[kk] + 32 * D * kb]);
-            acc[kb] = Mma<T>::mfma(a, qf[kk], acc[kb]);
+        for (int n = 0; n < C::CPR / NW; ++n)
+            __builtin_amdgcn_global_load_lds((gptr_t)(vt + (dl.v0 + 512 * n)),
+                                             (lptr_t)(vs + (wave * (C::CPR / NW) + n) * 512), 16,
+                                             0, 0);
+    } else {
+#pragma unroll 1
+        for (int n = 0; n < C::CPR / NW; ++n) {
+            const int inst = wave * (C::CPR / NW) + n;
+            const int slot = inst * 64 + lane;
+            const int row = slot / C::CPR;
+            const int cs = slot % C::CPR;
+            const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
+            __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
+                                             (lptr_t)(vs + inst * 512), 16, 0, 0);
         }
+    }
 }
 
 // 8 keys x 1 column of V as an MFMA operand through the transposing LDS read (see
@@ -182,112 +158,84 @@ template <int D> struct TileRegs {
     float lam, beta;        // Alg. 2 state: running max m, running sum l
 };
 
-// One key tile: scores, per-row state update, U += P V.  ks/vs: the tile in LDS.
+constexpr int kAhead = 8;         // operand reads in flight ahead of the matrix instructions
+
+// Phase 1 of a tile: raw scores S^T = K Q^T (two 32-key blocks, chains interleaved).
+// Operand reads run kAhead products ahead of the matrix instructions that consume them
+// (LDS returns in order).
+template <typename T, int D>
+__device__ __forceinline__ void phase_scores(const uint16_t* ks, const TileRegs<D>& g,
+                                             f32x16 (&acc)[2]) {
+    constexpr int NK = 2 * (D / 16);      // K operands / score products per tile
+    u32x4 ka[NK];
+#pragma unroll
+    for (int m = 0; m < kAhead; ++m)
+        ka[m] = *reinterpret_cast<const u32x4*>(&ks[g.kaddr[m >> 1] + 32 * D * (m & 1)]);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NK; ++m) {
+        acc[m & 1] = Mma<T>::mfma(ka[m], g.qf[m >> 1], acc[m & 1]);
+        if (m + kAhead < NK)
+            ka[m + kAhead] = *reinterpret_cast<const u32x4*>(
+                &ks[g.kaddr[(m + kAhead) >> 1] + 32 * D * ((m + kAhead) & 1)]);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+    for (int m = 0; m < NK - kAhead; ++m) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Phase 2: coefficients of the tile from its raw scores (per-row state update) and, where
+// the variant needs it, the scaling of U.  The raw scores are left untouched.
 template <typename T, int D, bool ONLINE>
-__device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t* vs,
+__device__ __forceinline__ void phase_coeffs(const f32x16 (&acc)[2], u32x4 (&bfrag)[4],
                                              TileRegs<D>& g, int j0, int hh, int lane, int nvis,
                                              bool need_mask, float c_log2) {
     constexpr int NDB = D / 32;
-    const float ninf = -__builtin_inff();
-    // Operand reads run kAhead products ahead of the matrix instructions that consume them
-    // (LDS returns in order), and V's first operands are requested before the per-row
-    // arithmetic so that their latency hides behind it.
-    constexpr int NK = 2 * (D / 16);      // K operands / score products per tile
-    constexpr int NV = 4 * NDB;           // V operands / output products per tile
-    constexpr int kAhead = 8;
-    f32x16 acc[2];
-    {
-        u32x4 ka[NK];
-#pragma unroll
-        for (int m = 0; m < kAhead; ++m)
-            ka[m] = *reinterpret_cast<const u32x4*>(&ks[g.kaddr[m >> 1] + 32 * D * (m & 1)]);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[kb][r] = 0.0f;
-#pragma unroll
-        for (int m = 0; m < NK; ++m) {
-            acc[m & 1] = Mma<T>::mfma(ka[m], g.qf[m >> 1], acc[m & 1]);
-            if (m + kAhead < NK)
-                ka[m + kAhead] = *reinterpret_cast<const u32x4*>(
-                    &ks[g.kaddr[(m + kAhead) >> 1] + 32 * D * ((m + kAhead) & 1)]);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-        for (int m = 0; m < NK - kAhead; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    u32x4 va[NV];
-#pragma unroll
-    for (int m = 0; m < kAhead; ++m)
-        va[m] = tile_v_operand<D>(vs, g.vaddr[m % NDB], 16 * (m / NDB));
-    __builtin_amdgcn_sched_barrier(0);
     const int jb = j0 + 4 * hh;
-
     if (!ONLINE) {
-        float ref;
         bool risky;
-        if (need_mask) risky = lazy_spec<T, 2, true>(acc, g.st, c_log2, jb, nvis, lane, ref);
-        else risky = lazy_spec<T, 2, false>(acc, g.st, c_log2, jb, nvis, lane, ref);
+        if (need_mask)
+            risky = lazy_spec_pack<T, 2, true, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
+        else
+            risky = lazy_spec_pack<T, 2, false, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
         if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // rare: redo the tile from recomputed raw scores, one 32-key block at a time
-            f32x16 raw;
-            float ll = ninf;
-#pragma unroll 1
-            for (int kb = 0; kb < 2; ++kb) {
-                tile_scores_block<T, D>(ks, g.qf, g.kaddr, kb, raw);
-                lazy_chain_block(raw, ll, c_log2, need_mask, jb + 32 * kb, nvis);
-            }
-            float ref_new;
-            const float f = lazy_new_state(g.st, risky, ll, ref_new);
-            const bool none = risky && g.st.one == 0.0f;
-            if (risky) ref = ref_new;
-            tile_scores_block<T, D>(ks, g.qf, g.kaddr, 0, raw);
-            lazy_apply_block(acc[0], raw, ref, c_log2, need_mask, jb, nvis, none);
-            tile_scores_block<T, D>(ks, g.qf, g.kaddr, 1, raw);
-            lazy_apply_block(acc[1], raw, ref, c_log2, need_mask, jb + 32, nvis, none);
+            // rare: flagged rows redo the tile with the key-by-key sigmoid recurrence
+            const float f =
+                lazy_redo_pack<T, 2>(acc, bfrag, g.st, risky, c_log2, need_mask, jb, nvis);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
         }
     } else {
-        if (need_mask) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float s = acc[kb][r] * c_log2;
-                    if ((jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
-                    acc[kb][r] = s;
-                }
-        } else {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[kb][r] *= c_log2;
-        }
-        const float f = row_step<T, 2, true>(acc, g.lam, g.beta);
+        float f;
+        if (need_mask) f = online_pack<T, 2, true>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
+        else f = online_pack<T, 2, false>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
     }
+}
 
-    // ---- U <- U + P V   (O^T = V^T P^T)
-    __builtin_amdgcn_sched_barrier(0);
-    u32x4 bfrag[4];
+// Phase 3: U <- U + P V   (O^T = V^T P^T)
+template <typename T, int D>
+__device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
+                                             const u32x4 (&bfrag)[4]) {
+    constexpr int NDB = D / 32;
+    constexpr int NV = 4 * NDB;           // V operands / output products per tile
+    u32x4 va[NV];
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-        f32x8 pv;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pv[e] = acc[g4 >> 1][8 * (g4 & 1) + e];
-        bfrag[g4] = Mma<T>::pack8(pv);
-    }
+    for (int m = 0; m < kAhead; ++m)
+        va[m] = tile_v_operand<D>(vs, g.vaddr[m % NDB], 16 * (m / NDB));
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
         g.U[m % NDB] = Mma<T>::mfma(va[m], bfrag[m / NDB], g.U[m % NDB]);
@@ -295,31 +243,38 @@ __device__ __forceinline__ void tile_compute(const uint16_t* ks, const uint16_t*
             va[m + kAhead] =
                 tile_v_operand<D>(vs, g.vaddr[(m + kAhead) % NDB], 16 * ((m + kAhead) / NDB));
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
     if (NV > kAhead) {
 #pragma unroll
         for (int m = 0; m < NV - kAhead; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
-// NW wavefronts of 32 query rows each per workgroup; two wavefronts per SIMD either way
-// (NW = 4: two workgroups per compute unit, NW = 8: one).
+// NW wavefronts of 32 query rows each per workgroup, two wavefronts per SIMD either way.
+//   NW = 4: two workgroups per compute unit; K and V tiles double-buffered, the copies of
+//           tile t+1 run during the math of tile t.
+//   NW = 8: one workgroup per compute unit (half the K/V traffic into LDS per unit of
+//           work); three buffers each, the copies run two tiles ahead.
 template <typename T, int D, bool ONLINE, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW)
 void tile_kernel(Problem p) {
     using C = TileCfg<D>;
+    constexpr int NBUF = NW == 8 ? 3 : 2;     // buffers per tensor
+    constexpr int AHEAD = NBUF - 1;           // tiles the copies run ahead of the math
+    constexpr int NCP = 2 * (C::CPR / NW);    // copy instructions per wavefront and tile
     constexpr int kBM = 32 * NW;      // query rows per workgroup
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
-    // two buffers of a K tile and a V tile each
-    __shared__ __align__(1024) uint16_t lds[4 * kBC * D];
-    uint16_t* const k0s = lds;
-    uint16_t* const v0s = lds + kBC * D;
-    uint16_t* const k1s = lds + 2 * kBC * D;
-    uint16_t* const v1s = lds + 3 * kBC * D;
+    constexpr int kTile = kBC * D;    // elements of one K or V tile
+    // tile t lives in buffer t % NBUF of its tensor
+    __shared__ __align__(1024) uint16_t lds[2 * NBUF * kTile];
+    uint16_t* const kbuf = lds;
+    uint16_t* const vbuf = lds + NBUF * kTile;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -359,9 +314,17 @@ void tile_kernel(Problem p) {
     const int per_split = (tiles_all + p.splits - 1) / p.splits;
     const int t_begin = sp * per_split;
     const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
+    const int n = max(t_end - t_begin, 0);          // tiles of this workgroup
+    const int jbase = t_begin * kBC;                // first key of tile 0
 
+    // prologue copies: the first AHEAD tiles
     const DmaLane<D, NW> dl(wave, lane);
-    if (t_begin < t_end) tile_copy<D, NW>(kg, vg, t_begin * kBC, p.Lk, dl, wave, lane, k0s, v0s);
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if (t < n) {
+            tile_copy_k<D, NW>(kg, jbase + t * kBC, p.Lk, dl, wave, lane, kbuf + t * kTile);
+            tile_copy_v<D, NW>(vg, jbase + t * kBC, p.Lk, dl, wave, lane, vbuf + t * kTile);
+        }
 
     TileRegs<D> g;
     {
@@ -396,26 +359,34 @@ void tile_kernel(Problem p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // two tiles per trip so that each half works on fixed buffers
-    for (int kt = t_begin; kt < t_end; kt += 2) {
-        {
-            const int j0 = kt * kBC;
-            if (kt + 1 < t_end) tile_copy<D, NW>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k1s, v1s);
-            if (j0 < wave_nvis_max)
-                tile_compute<T, D, ONLINE>(k0s, v0s, g, j0, hh, lane, nvis,
-                                           j0 + kBC > wave_nvis_min, c_log2);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+    // Period t: start the copies of tile t + AHEAD (its buffers were last read in period
+    // t - 1), do the math of tile t, wait until tile t + 1 has landed (the copies started
+    // in this period may stay in flight when AHEAD = 2), barrier.
+    for (int t = 0; t < n; ++t) {
+        const int j0 = jbase + t * kBC;
+        const int ta = t + AHEAD;
+        if (ta < n) {
+            tile_copy_k<D, NW>(kg, jbase + ta * kBC, p.Lk, dl, wave, lane,
+                               kbuf + (ta % NBUF) * kTile);
+            tile_copy_v<D, NW>(vg, jbase + ta * kBC, p.Lk, dl, wave, lane,
+                               vbuf + (ta % NBUF) * kTile);
         }
-        if (kt + 1 < t_end) {
-            const int j0 = (kt + 1) * kBC;
-            if (kt + 2 < t_end) tile_copy<D, NW>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, k0s, v0s);
-            if (j0 < wave_nvis_max)
-                tile_compute<T, D, ONLINE>(k1s, v1s, g, j0, hh, lane, nvis,
-                                           j0 + kBC > wave_nvis_min, c_log2);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+        if (j0 < wave_nvis_max) {
+            f32x16 acc[2];
+            u32x4 bfrag[4];
+            phase_scores<T, D>(kbuf + (t % NBUF) * kTile, g, acc);
+            phase_coeffs<T, D, ONLINE>(acc, bfrag, g, j0, hh, lane, nvis,
+                                       j0 + kBC > wave_nvis_min, c_log2);
+            phase_output<T, D>(vbuf + (t % NBUF) * kTile, g, bfrag);
         }
+        if (AHEAD == 2 && ta < n) {
+            if constexpr (NCP == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else if constexpr (NCP == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
     }
 
     // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
