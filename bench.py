@@ -21,6 +21,12 @@ import torch
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 
+# HBM-side bytes per launch of the dominant kernel, from the profiler's FETCH_SIZE and
+# WRITE_SIZE counters scaled by a 1 GiB device copy (the summaries under profiles/ give the
+# commands and the raw readings); they cannot be read from inside this process.
+TRAFFIC_PREFILL_BYTES = 738.2e6
+TRAFFIC_DECODE_BYTES = 2150.8e6
+
 
 def time_calls(fn, steps, warmup, nsets):
     """Wall time and HIP-event time (on the launch stream) of `steps` calls of fn(i % nsets)."""
@@ -48,6 +54,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
     ap.add_argument("--no-ablation", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of 1 GiB, 10 times (reference for "
+                         "scaling the profiler's HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU; this build has no multi-GPU path (--gpus must be 1)",
@@ -56,6 +65,16 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30,
+                                               "launches": 10}}))
+        return 0
 
     from paper_2505_14201_amd import flashd, synthetic
 
@@ -92,7 +111,8 @@ def main() -> int:
                    "flop_per_step": flops},
         "roofline": {"bound": "mfma", "kernel": "tile_kernel<BF16,128> (flashd_attn_fwd)",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": TRAFFIC_PREFILL_BYTES,
                      "kernel_ms": round(kern_ms, 4)},
     }
 
@@ -141,7 +161,8 @@ def main() -> int:
                          "bytes_per_step": wd.bytes_io(),
                          "roofline": {"bound": "hbm", "achieved": round(gbs, 1),
                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                      "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}}
+                                      "frac": round(gbs / PEAK_HBM_GBS, 4),
+                                      "traffic": TRAFFIC_DECODE_BYTES}}
     print(json.dumps(out))
     return 0
 
