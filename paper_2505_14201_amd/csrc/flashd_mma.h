@@ -51,12 +51,14 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
 // log2(2^a + 2^b) through 2^{-|a-b|} <= 1 (the saturating side of the sigmoid);
-// -inf is the empty run.
+// -inf is the empty run.  Branch-free: with one side -inf the correction term is
+// log2(1 + 0) = 0 and the other side comes back unchanged; only (-inf, -inf), where
+// a - b is NaN, needs the select.
 __device__ __forceinline__ float lse2(float a, float b) {
     const float ninf = -__builtin_inff();
-    if (a == ninf) return b;
-    if (b == ninf) return a;
-    return fmaxf(a, b) + log2_fast(1.0f + exp2_fast(-fabsf(a - b)));
+    const float m = fmaxf(a, b);
+    const float r = m + log2_fast(1.0f + exp2_fast(-fabsf(a - b)));
+    return m == ninf ? ninf : r;
 }
 
 // 8 keys x 1 column of a row-major [key][d] LDS tile as an MFMA operand, through the
@@ -246,6 +248,10 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
             psum += pv[e];
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        // Keep the groups apart: scheduled together, the 32 exponents and 32 results of a
+        // tile are all live at once, and the register allocator then starts to move the
+        // accumulators around.  Eight independent elements are enough to hide latencies.
+        __builtin_amdgcn_sched_barrier(0);
     }
     psum = pair_sum(psum);
     const bool safe = psum <= LazyLimit<T>::kMaxPsum;             // false for inf and NaN
@@ -276,13 +282,20 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
                                                 LazyRow& st, bool risky, float c_log2,
                                                 bool need_mask, int jb, int nvis) {
     const float ninf = -__builtin_inff();
+    // The mask compares are redone here from values the compiler cannot connect with the
+    // ones of lazy_spec_pack (empty asm); shared, 32 compare results would stay live
+    // across the branch into this rare path.
+    int nv1 = nvis, nv2 = nvis;
+    asm volatile("" : "+v"(nv1));
     float ll = ninf;
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const bool masked = need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis;
-            if (!masked) ll = lse2(ll, acc[kb][r] * c_log2);
+            const bool masked = need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nv1;
+            ll = lse2(ll, masked ? ninf : acc[kb][r] * c_log2);
+            // rare path: keep it sequential so that it does not add to the register need
+            if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
         }
     ll = lse2(ll, __shfl_xor(ll, 32, 64));                  // partner lane's run
     const bool empty = st.one == 0.0f;
@@ -299,6 +312,7 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
         st.R = ref;
         st.one = none ? 0.0f : 1.0f;
     }
+    asm volatile("" : "+v"(nv2));
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -307,11 +321,12 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
             const int r = 8 * (g & 1) + e;
             float x = fmaf(acc[g >> 1][r], c_log2, -ref);
             const bool masked =
-                need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis;
+                need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv2;
             if (masked || none) x = ninf;
             pv[e] = exp2_fast(x);
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        __builtin_amdgcn_sched_barrier(0);
     }
     return f;
 }
@@ -352,6 +367,7 @@ __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bf
             psum += pv[e];
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        __builtin_amdgcn_sched_barrier(0);
     }
     psum = pair_sum(psum);
     l = l * resc + psum;

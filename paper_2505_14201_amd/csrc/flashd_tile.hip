@@ -36,7 +36,7 @@
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
 
-#include <cstdlib>
+#include <algorithm>
 #include <type_traits>
 
 namespace flashd {
@@ -64,72 +64,76 @@ template <> struct TileCfg<64> {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Per-lane element offsets of the direct global->LDS copy.  Instruction n of a wavefront
-// (n < CPR/NW, NW wavefronts) moves 64 chunks of 16 bytes into 1 KB of LDS: lane l fills
-// chunk position cs = l % CPR of tile row (64/NW)*wave + n*(64/CPR) + l/CPR.  With the swizzles above the
-// global chunk to fetch is cs ^ (l >> 4) ^ 4n for K and cs ^ swz_v for V (independent of
-// n), so the offsets are (k0 ^ 32n) + 512n and v0 + 512n elements.
-template <int D, int NW> struct DmaLane {
-    int k0, v0;
+constexpr int kNW = 4;            // wavefronts per workgroup
+
+// Per-lane byte offsets of the direct global->LDS copy.  Instruction n of a wavefront
+// (n < NI = CPR/4) moves 64 chunks of 16 bytes into 1 KB of LDS: lane l fills chunk position
+// cs = l % CPR of tile row 16*wave + n*(64/CPR) + l/CPR.  With the swizzles above the global
+// chunk to fetch is cs ^ (l >> 4) ^ 4n for K and cs ^ swz_v for V (independent of n), so the
+// element offsets are (k0 ^ 32n) + 512n and v0 + 512n.  The + 512n (1 KB) is the same on
+// the global and on the LDS side and rides in the instruction's immediate offset, which is
+// added to both addresses.
+template <int D> struct DmaLane {
+    static constexpr int NI = TileCfg<D>::CPR / kNW;
+    uint32_t koff[NI], voff;
     __device__ __forceinline__ DmaLane(int wave, int lane) {
         using C = TileCfg<D>;
-        const int row = (kBC / NW) * wave + lane / C::CPR;     // row of this lane for n = 0
+        const int row = (kBC / kNW) * wave + lane / C::CPR;     // row of this lane for n = 0
         const int cs = lane % C::CPR;
-        k0 = row * D + 8 * (cs ^ C::swz_k(row));
-        v0 = row * D + 8 * (cs ^ C::swz_v(row));
+        const int k0 = row * D + 8 * (cs ^ C::swz_k(row));
+#pragma unroll
+        for (int n = 0; n < NI; ++n) koff[n] = 2u * (uint32_t)(k0 ^ (32 * n));
+        voff = 2u * (uint32_t)(row * D + 8 * (cs ^ C::swz_v(row)));
     }
 };
 
-// Start the copy of the K (or V) tile whose first key is j0.  A tile that sticks out past
-// the last key takes the slow form with rows clamped to the last key (masked later).
-template <int D, int NW>
-__device__ __forceinline__ void tile_copy_k(const uint16_t* kg, int j0, int Lk,
-                                            const DmaLane<D, NW>& dl, int wave, int lane,
-                                            uint16_t* ks) {
+template <int N> struct IntC { static constexpr int value = N; };
+
+// Start the copy of the K and V tiles whose first key is j0 into ks / vs (the wavefront
+// fills its own 16 rows of each).  A tile that sticks out past the last key takes the slow
+// form with rows clamped to the last key (masked later).
+template <int D>
+__device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
+                                          const DmaLane<D>& dl, int wave, int lane,
+                                          uint16_t* ks, uint16_t* vs) {
     using C = TileCfg<D>;
+    constexpr int NI = DmaLane<D>::NI;
+    uint16_t* kw = ks + wave * (NI * 512);
+    uint16_t* vw = vs + wave * (NI * 512);
     if (j0 + kBC <= Lk) {
-        const uint16_t* kt = kg + (size_t)j0 * D;       // wavefront-uniform tile base
-#pragma unroll
-        for (int n = 0; n < C::CPR / NW; ++n)
-            __builtin_amdgcn_global_load_lds((gptr_t)(kt + ((dl.k0 ^ (32 * n)) + 512 * n)),
-                                             (lptr_t)(ks + (wave * (C::CPR / NW) + n) * 512), 16,
-                                             0, 0);
+        // wavefront-uniform tile bases, 32-bit lane offsets
+        const char* kt = reinterpret_cast<const char*>(kg + (size_t)j0 * D);
+        const char* vt = reinterpret_cast<const char*>(vg + (size_t)j0 * D);
+        // The empty asm keeps the 32-bit offsets from being widened outside the loop, so
+        // that each copy is one instruction with a scalar base and a 32-bit lane offset.
+        auto issue = [&](auto n) {
+            constexpr int N = decltype(n)::value;
+            uint32_t off = dl.koff[N];
+            asm volatile("" : "+v"(off));
+            __builtin_amdgcn_global_load_lds((gptr_t)(kt + off), (lptr_t)kw, 16, 1024 * N, 0);
+        };
+        uint32_t voff = dl.voff;
+        asm volatile("" : "+v"(voff));
+        auto issue_v = [&](auto n) {
+            constexpr int N = decltype(n)::value;
+            __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff), (lptr_t)vw, 16, 1024 * N, 0);
+        };
+        issue(IntC<0>{}); issue(IntC<1>{});
+        if constexpr (NI == 4) { issue(IntC<2>{}); issue(IntC<3>{}); }
+        issue_v(IntC<0>{}); issue_v(IntC<1>{});
+        if constexpr (NI == 4) { issue_v(IntC<2>{}); issue_v(IntC<3>{}); }
     } else {
 #pragma unroll 1
-        for (int n = 0; n < C::CPR / NW; ++n) {
-            const int inst = wave * (C::CPR / NW) + n;
+        for (int n = 0; n < NI; ++n) {
+            const int inst = wave * NI + n;
             const int slot = inst * 64 + lane;
             const int row = slot / C::CPR;
             const int cs = slot % C::CPR;
             const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
             __builtin_amdgcn_global_load_lds((gptr_t)(kg + grow + 8 * (cs ^ C::swz_k(row))),
-                                             (lptr_t)(ks + inst * 512), 16, 0, 0);
-        }
-    }
-}
-
-template <int D, int NW>
-__device__ __forceinline__ void tile_copy_v(const uint16_t* vg, int j0, int Lk,
-                                            const DmaLane<D, NW>& dl, int wave, int lane,
-                                            uint16_t* vs) {
-    using C = TileCfg<D>;
-    if (j0 + kBC <= Lk) {
-        const uint16_t* vt = vg + (size_t)j0 * D;
-#pragma unroll
-        for (int n = 0; n < C::CPR / NW; ++n)
-            __builtin_amdgcn_global_load_lds((gptr_t)(vt + (dl.v0 + 512 * n)),
-                                             (lptr_t)(vs + (wave * (C::CPR / NW) + n) * 512), 16,
-                                             0, 0);
-    } else {
-#pragma unroll 1
-        for (int n = 0; n < C::CPR / NW; ++n) {
-            const int inst = wave * (C::CPR / NW) + n;
-            const int slot = inst * 64 + lane;
-            const int row = slot / C::CPR;
-            const int cs = slot % C::CPR;
-            const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
+                                             (lptr_t)(kw + n * 512), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
-                                             (lptr_t)(vs + inst * 512), 16, 0, 0);
+                                             (lptr_t)(vw + n * 512), 16, 0, 0);
         }
     }
 }
@@ -193,23 +197,30 @@ __device__ __forceinline__ void phase_scores(const uint16_t* ks, const TileRegs<
 }
 
 // Phase 2: coefficients of the tile from its raw scores (per-row state update) and, where
-// the variant needs it, the scaling of U.  The raw scores are left untouched.
+// the variant needs it, the scaling of U.  general = false promises that every key of the
+// tile is visible to every row of the wavefront and that no row is still empty (not the
+// first tile of a row); the common code path then carries neither the mask nor the
+// first-key logic.
 template <typename T, int D, bool ONLINE>
-__device__ __forceinline__ void phase_coeffs(const f32x16 (&acc)[2], u32x4 (&bfrag)[4],
-                                             TileRegs<D>& g, int j0, int hh, int lane, int nvis,
-                                             bool need_mask, float c_log2) {
+__device__ __forceinline__ void phase_coeffs(const uint16_t* ks, const f32x16 (&acc)[2],
+                                             u32x4 (&bfrag)[4], TileRegs<D>& g, int j0, int hh,
+                                             int lane, int nvis, bool general, float c_log2) {
     constexpr int NDB = D / 32;
     const int jb = j0 + 4 * hh;
     if (!ONLINE) {
         bool risky;
-        if (need_mask)
+        if (general)
             risky = lazy_spec_pack<T, 2, true, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
         else
-            risky = lazy_spec_pack<T, 2, false, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
+            risky = lazy_spec_pack<T, 2, false, false>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
         if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // rare: flagged rows redo the tile with the key-by-key sigmoid recurrence
+            // rare: flagged rows redo the tile with the key-by-key sigmoid recurrence.  The
+            // raw scores are formed again (K is still in LDS) rather than kept: holding them
+            // until here would cost the common path 32 registers.
+            f32x16 acc2[2];
+            phase_scores<T, D>(ks, g, acc2);
             const float f =
-                lazy_redo_pack<T, 2>(acc, bfrag, g.st, risky, c_log2, need_mask, jb, nvis);
+                lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -217,7 +228,7 @@ __device__ __forceinline__ void phase_coeffs(const f32x16 (&acc)[2], u32x4 (&bfr
         }
     } else {
         float f;
-        if (need_mask) f = online_pack<T, 2, true>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
+        if (general) f = online_pack<T, 2, true>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
         else f = online_pack<T, 2, false>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
@@ -255,26 +266,69 @@ __device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// NW wavefronts of 32 query rows each per workgroup, two wavefronts per SIMD either way.
-//   NW = 4: two workgroups per compute unit; K and V tiles double-buffered, the copies of
-//           tile t+1 run during the math of tile t.
-//   NW = 8: one workgroup per compute unit (half the K/V traffic into LDS per unit of
-//           work); three buffers each, the copies run two tiles ahead.
-template <typename T, int D, bool ONLINE, int NW>
-__global__ __launch_bounds__(NW * 64, 8 / NW)
-void tile_kernel(Problem p) {
+// How workgroup ids map to work (set by the launcher).
+struct TileSched {
+    int pair;          // 1: a workgroup does row tiles (m_tiles - 1 - r) and r of its unit
+    int wg_per_unit;   // workgroups per (split, b, h) unit
+    int nx;            // 8: unit u runs on XCD u % 8 (ids go round-robin over the XCDs); 1: no such mapping
+    int group;         // units of one XCD that are in flight together
+};
+
+// One row tile of one unit as seen by a wavefront and by a lane.
+struct Item {                   // all members are wavefront-uniform
+    int m0, wrow0;              // first row of the workgroup / of the wavefront
+    int wmax, wmin;             // most / fewest keys visible to a row of the wavefront
+    int n;                      // key tiles of this item (within the workgroup's split)
+    int jbase;                  // first key of tile 0
+};
+
+template <int D>
+__device__ __forceinline__ Item make_item(const Problem& p, int mt, int sp, int wave) {
+    constexpr int kBM = 32 * kNW;
+    Item it;
+    it.m0 = mt * kBM;
+    it.wrow0 = it.m0 + wave * 32;
+    it.wmax = it.wrow0 < p.Lq ? visible_count(p, min(it.wrow0 + 31, p.Lq - 1)) : 0;
+    it.wmin = (it.wrow0 + 31 < p.Lq) ? visible_count(p, it.wrow0) : 0;
+    const int blk_nvis = visible_count(p, min(it.m0 + kBM - 1, p.Lq - 1));
+    const int tiles_all = (p.Lk + kBC - 1) / kBC;
+    const int per_split = (tiles_all + p.splits - 1) / p.splits;
+    const int t_begin = sp * per_split;
+    const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
+    it.n = max(t_end - t_begin, 0);
+    it.jbase = t_begin * kBC;
+    return it;
+}
+
+// The three phases of one tile, with the LDS slot (PAR) a compile-time constant so that
+// every operand address is a register plus an immediate.  general: keys may be masked or
+// rows may still be empty.
+template <typename T, int D, bool ONLINE, int PAR>
+__device__ __forceinline__ void tile_math(const uint16_t* lds, TileRegs<D>& g, int j0, int hh,
+                                          int lane, int nvis, bool general, float c_log2) {
+    constexpr int kTile = kBC * D;
+    f32x16 acc[2];
+    u32x4 bfrag[4];
+    phase_scores<T, D>(lds + PAR * kTile, g, acc);
+    phase_coeffs<T, D, ONLINE>(lds + PAR * kTile, acc, bfrag, g, j0, hh, lane, nvis, general,
+                               c_log2);
+    phase_output<T, D>(lds + (2 + PAR) * kTile, g, bfrag);
+}
+
+// 4 wavefronts of 32 query rows each per workgroup, two workgroups per compute unit.  K and
+// V tiles are double-buffered in LDS ([K0 K1 V0 V1]); the copies of tile t+1 run during
+// the math of tile t, one barrier per tile.  A workgroup may own two row tiles (a long and a
+// short one under a causal mask, so that all workgroups carry the same work); the copy
+// pipeline runs on across the change of row tile.
+template <typename T, int D, bool ONLINE>
+__global__ __launch_bounds__(kNW * 64, 2)
+void tile_kernel(Problem p, TileSched sc) {
     using C = TileCfg<D>;
-    constexpr int NBUF = NW == 8 ? 3 : 2;     // buffers per tensor
-    constexpr int AHEAD = NBUF - 1;           // tiles the copies run ahead of the math
-    constexpr int NCP = 2 * (C::CPR / NW);    // copy instructions per wavefront and tile
-    constexpr int kBM = 32 * NW;      // query rows per workgroup
+    constexpr int kBM = 32 * kNW;     // query rows per workgroup
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int kTile = kBC * D;    // elements of one K or V tile
-    // tile t lives in buffer t % NBUF of its tensor
-    __shared__ __align__(1024) uint16_t lds[2 * NBUF * kTile];
-    uint16_t* const kbuf = lds;
-    uint16_t* const vbuf = lds + NBUF * kTile;
+    __shared__ __align__(1024) uint16_t lds[4 * kTile];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -282,21 +336,34 @@ void tile_kernel(Problem p) {
     const int col = lane & 31;
     const int hh = lane >> 5;
 
-    // workgroup id -> (row tile, split, b, h); the row tile is the slowest index
+    // workgroup id -> (unit, rank of the row tile within the unit)
     const int m_tiles = (p.Lq + kBM - 1) / kBM;
     const int n_bh = p.B * p.Hq;
-    const int per_rank = n_bh * p.splits;
-    const int mt_rank = blockIdx.x / per_rank;
-    const int rem = blockIdx.x % per_rank;
-    const int sp = rem / n_bh;
-    const int bh = rem % n_bh;
+    const int xcd = blockIdx.x % sc.nx;
+    const int local = blockIdx.x / sc.nx;
+    const int nux = (n_bh * p.splits) / sc.nx;         // units on this XCD
+    const int gw = sc.group * sc.wg_per_unit;
+    const int grp = local / gw;
+    const int within = local % gw;
+    const int gsz = min(sc.group, nux - grp * sc.group);
+    const int rank = within / gsz;                      // slowest inside a group
+    const int unit = xcd + sc.nx * (grp * sc.group + within % gsz);
+    const int sp = unit / n_bh;
+    const int bh = unit % n_bh;
     const int b = bh / p.Hq;
     const int h = bh % p.Hq;
-    const int mt = p.causal ? m_tiles - 1 - mt_rank : mt_rank;     // longest rows first
     const int kvh = h / (p.Hq / p.Hkv);
-    const int m0 = mt * kBM;
-    const int wrow0 = m0 + wave * 32;
-    const int my_row = wrow0 + col;
+    // row tiles of this workgroup: the longest first
+    int mt_of[2];
+    int n_items = 1;
+    if (sc.pair) {
+        mt_of[0] = m_tiles - 1 - rank;
+        mt_of[1] = rank;
+        n_items = mt_of[0] != mt_of[1] ? 2 : 1;
+    } else {
+        mt_of[0] = p.causal ? m_tiles - 1 - rank : rank;
+        mt_of[1] = 0;
+    }
 
     const uint16_t* qg = static_cast<const uint16_t*>(p.q) +
                          ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
@@ -304,35 +371,19 @@ void tile_kernel(Problem p) {
                          ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
     const uint16_t* vg = static_cast<const uint16_t*>(p.v) +
                          ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
+    uint16_t* og = static_cast<uint16_t*>(p.o) + ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
 
-    const int nvis = visible_count(p, my_row);
-    const bool wave_live = wrow0 < p.Lq;
-    const int wave_nvis_max = wave_live ? visible_count(p, min(wrow0 + 31, p.Lq - 1)) : 0;
-    const int wave_nvis_min = (wrow0 + 31 < p.Lq) ? visible_count(p, wrow0) : 0;
-    const int blk_nvis = visible_count(p, min(m0 + kBM - 1, p.Lq - 1));
-    const int tiles_all = (p.Lk + kBC - 1) / kBC;
-    const int per_split = (tiles_all + p.splits - 1) / p.splits;
-    const int t_begin = sp * per_split;
-    const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
-    const int n = max(t_end - t_begin, 0);          // tiles of this workgroup
-    const int jbase = t_begin * kBC;                // first key of tile 0
-
-    // prologue copies: the first AHEAD tiles
-    const DmaLane<D, NW> dl(wave, lane);
-#pragma unroll
-    for (int t = 0; t < AHEAD; ++t)
-        if (t < n) {
-            tile_copy_k<D, NW>(kg, jbase + t * kBC, p.Lk, dl, wave, lane, kbuf + t * kTile);
-            tile_copy_v<D, NW>(vg, jbase + t * kBC, p.Lk, dl, wave, lane, vbuf + t * kTile);
-        }
+    const DmaLane<D> dl(wave, lane);
+    Item cur = make_item<D>(p, mt_of[0], sp, wave);
+    int nvis = visible_count(p, cur.wrow0 + col);      // keys visible to the lane's row
+    bool have0 = false;          // tile 0 of the current item is in flight or has landed
+    if (cur.n > 0) {
+        tile_copy<D>(kg, vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
+        have0 = true;
+    }
 
     TileRegs<D> g;
     {
-        // Q fragments: B operand of S^T = K Q^T, kept for the whole kernel
-        const int qr = min(my_row, p.Lq - 1);
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
-            g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
         // operand addresses inside a tile (elements)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
@@ -344,154 +395,192 @@ void tile_kernel(Problem p) {
         for (int i = 0; i < NDB; ++i)
             g.vaddr[i] = (4 * hh + tq) * D +
                          8 * ((4 * i + 2 * half + ((t & 3) >> 1)) ^ C::swz_v(tq)) + 4 * (t & 1);
+        // Q fragments: B operand of S^T = K Q^T, kept for the whole row tile
+        const int qr = min(cur.wrow0 + col, p.Lq - 1);
 #pragma unroll
-        for (int i = 0; i < NDB; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) g.U[i][r] = 0.0f;
-        g.st = {0.0f, 1.0f, 0.0f};
-        g.lam = -__builtin_inff();
-        g.beta = 0.0f;
+        for (int kk = 0; kk < NKK; ++kk)
+            g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
     }
 
     const float c_log2 = p.scale * kLog2e;        // scores are carried in log2 units
     const float ninf = -__builtin_inff();
 
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    for (int item = 0; item < n_items; ++item) {
+        Item nxt;
+        nxt.n = 0;
+        if (item + 1 < n_items) nxt = make_item<D>(p, mt_of[1], sp, wave);
+#pragma unroll
+        for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) g.U[i][r] = 0.0f;
+        g.st = {0.0f, 1.0f, 0.0f};
+        g.lam = ninf;
+        g.beta = 0.0f;
 
-    // Period t: start the copies of tile t + AHEAD (its buffers were last read in period
-    // t - 1), do the math of tile t, wait until tile t + 1 has landed (the copies started
-    // in this period may stay in flight when AHEAD = 2), barrier.
-    for (int t = 0; t < n; ++t) {
-        const int j0 = jbase + t * kBC;
-        const int ta = t + AHEAD;
-        if (ta < n) {
-            tile_copy_k<D, NW>(kg, jbase + ta * kBC, p.Lk, dl, wave, lane,
-                               kbuf + (ta % NBUF) * kTile);
-            tile_copy_v<D, NW>(vg, jbase + ta * kBC, p.Lk, dl, wave, lane,
-                               vbuf + (ta % NBUF) * kTile);
-        }
-        if (j0 < wave_nvis_max) {
-            f32x16 acc[2];
-            u32x4 bfrag[4];
-            phase_scores<T, D>(kbuf + (t % NBUF) * kTile, g, acc);
-            phase_coeffs<T, D, ONLINE>(acc, bfrag, g, j0, hh, lane, nvis,
-                                       j0 + kBC > wave_nvis_min, c_log2);
-            phase_output<T, D>(vbuf + (t % NBUF) * kTile, g, bfrag);
-        }
-        if (AHEAD == 2 && ta < n) {
-            if constexpr (NCP == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else if constexpr (NCP == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        } else {
+        if (!have0 && cur.n > 0)
+            tile_copy<D>(kg, vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
+        if (item == 0 || !have0) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
         }
-        __syncthreads();
-    }
+        have0 = false;
 
-    // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
-    float fin, lam_out;
-    if (!ONLINE) {
-        fin = g.st.beta;
-        lam_out = g.st.one == 0.0f ? ninf : g.st.R - log2_fast(g.st.beta);
-    } else {
-        row_finish<true>(g.lam, g.beta, fin, lam_out);
-    }
-    if (p.splits == 1) {
-        // Stage the wavefront's 32 x D output block through LDS (the tile buffers are idle
-        // after the last barrier; each wavefront uses its own 32 * D elements) so that the
-        // global stores are 16 bytes per lane and whole rows are contiguous.  Chunk c of
-        // row r sits at chunk position c ^ (r % CPR) to keep the 8-byte writes and the
-        // 16-byte reads off each other's banks.
-        uint16_t* stage = lds + wave * (32 * D);
-#pragma unroll
-        for (int i = 0; i < NDB; ++i)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int dc = 32 * i + 8 * gq + 4 * hh;            // 4 consecutive columns
-                uint16_t h4[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if constexpr (std::is_same<T, BF16>::value)
-                        h4[e] = f32_to_bf16(g.U[i][4 * gq + e] * fin);
-                    else
-                        h4[e] = __builtin_bit_cast(uint16_t,
-                                                   static_cast<_Float16>(g.U[i][4 * gq + e] * fin));
-                }
-                const int chunk = (dc >> 3) ^ (col % C::CPR);
-                u32x2 w2;
-                w2[0] = (uint32_t)h4[0] | ((uint32_t)h4[1] << 16);
-                w2[1] = (uint32_t)h4[2] | ((uint32_t)h4[3] << 16);
-                *reinterpret_cast<u32x2*>(&stage[col * D + 8 * chunk + (dc & 4)]) = w2;
+        // Period t: start the copies of the next tile into the other slot, which was last
+        // read in period t - 1; do the math of tile t; wait for the copies; barrier.  Tile t
+        // of a row tile lives in slot t % 2, and the loop body is two periods, one per slot,
+        // so that each is compiled once with constant LDS addresses.  Tile 0 of the next
+        // row tile is copied during this row tile's last period if that leaves slot 0 free
+        // (an even number of tiles), else after it.
+        auto period = [&](auto slot, int t) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(slot)::value;
+            const int j0 = cur.jbase + t * kBC;
+            uint16_t* kdst = lds + (PAR ^ 1) * kTile;
+            if (t + 1 < cur.n) {
+                tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
+            } else if (PAR == 1 && nxt.n > 0) {
+                tile_copy<D>(kg, vg, nxt.jbase, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
+                have0 = true;
             }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        uint16_t* og = static_cast<uint16_t*>(p.o) + ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
-#pragma unroll
-        for (int n = 0; n < 32 * C::CPR / 64; ++n) {
-            const int slot = n * 64 + lane;
-            const int r = slot / C::CPR;
-            const int c = slot % C::CPR;
-            const u32x4 x =
-                *reinterpret_cast<const u32x4*>(&stage[r * D + 8 * (c ^ (r % C::CPR))]);
-            if (wrow0 + r < p.Lq)
-                *reinterpret_cast<u32x4*>(og + (size_t)(wrow0 + r) * D + 8 * c) = x;
+            if (j0 < cur.wmax)
+                tile_math<T, D, ONLINE, PAR>(lds, g, j0, hh, lane, nvis,
+                                             t == 0 || j0 + kBC > cur.wmin, c_log2);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        };
+        for (int t = 0; t < cur.n; t += 2) {
+            period(IntC<0>{}, t);
+            if (t + 1 < cur.n) period(IntC<1>{}, t + 1);
         }
-    } else if (my_row < p.Lq) {
-        // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
-        float* dst = p.ws +
-                     ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + my_row) * (D + 2);
+
+        // The next row tile's Q fragments: requested now, needed after the epilogue.
+        if (item + 1 < n_items) {
+            const int qr = min(nxt.wrow0 + col, p.Lq - 1);
 #pragma unroll
-        for (int i = 0; i < NDB; ++i)
+            for (int kk = 0; kk < NKK; ++kk)
+                g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
+        }
+
+        // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
+        float fin, lam_out;
+        if (!ONLINE) {
+            fin = g.st.beta;
+            lam_out = g.st.one == 0.0f ? ninf : g.st.R - log2_fast(g.st.beta);
+        } else {
+            row_finish<true>(g.lam, g.beta, fin, lam_out);
+        }
+        // The epilogue's lane arithmetic is kept inside the loop over row tiles (the empty asm
+        // hides that it is invariant): hoisted, its addresses would occupy registers during
+        // the tile loop.
+        int elane = lane;
+        asm volatile("" : "+v"(elane));
+        const int col = elane & 31;
+        const int hh = elane >> 5;
+        if (p.splits == 1) {
+            // Stage the wavefront's 32 x D output block through LDS so that the global
+            // stores are 16 bytes per lane and whole rows are contiguous.  Slot 1 is idle
+            // after the last barrier and never the target of the copy of the next row
+            // tile's first tile; the wavefront uses exactly the parts of it that its own
+            // copies fill (its 16 rows of the K tile for output rows 0..15, of the V tile
+            // for rows 16..31), so no other wavefront's copies or reads can touch them and
+            // no barrier is needed.  Chunk c of row r sits at chunk position c ^ (r % CPR)
+            // to keep the 8-byte writes and the 16-byte reads off each other's banks.
+            uint16_t* stage_k = lds + kTile + wave * (16 * D);
+            uint16_t* stage = col < 16 ? stage_k : stage_k + 2 * kTile;
+            const int srow = col & 15;
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int dc = 32 * i + 8 * gq + 4 * hh;
-                float4 x;
-                x.x = g.U[i][4 * gq + 0] * fin; x.y = g.U[i][4 * gq + 1] * fin;
-                x.z = g.U[i][4 * gq + 2] * fin; x.w = g.U[i][4 * gq + 3] * fin;
-                *reinterpret_cast<float4*>(dst + dc) = x;
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int dc = 32 * i + 8 * gq + 4 * hh;            // 4 consecutive columns
+                    uint16_t h4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if constexpr (std::is_same<T, BF16>::value)
+                            h4[e] = f32_to_bf16(g.U[i][4 * gq + e] * fin);
+                        else
+                            h4[e] = __builtin_bit_cast(
+                                uint16_t, static_cast<_Float16>(g.U[i][4 * gq + e] * fin));
+                    }
+                    const int chunk = (dc >> 3) ^ (col % C::CPR);
+                    u32x2 w2;
+                    w2[0] = (uint32_t)h4[0] | ((uint32_t)h4[1] << 16);
+                    w2[1] = (uint32_t)h4[2] | ((uint32_t)h4[3] << 16);
+                    *reinterpret_cast<u32x2*>(&stage[srow * D + 8 * chunk + (dc & 4)]) = w2;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int n = 0; n < 32 * C::CPR / 64; ++n) {
+                const int slot = n * 64 + elane;
+                const int r = slot / C::CPR;                // output row within the wavefront
+                const int c = slot % C::CPR;
+                const uint16_t* src = (r < 16 ? stage_k : stage_k + 2 * kTile) +
+                                      (r & 15) * D + 8 * (c ^ (r % C::CPR));
+                const u32x4 x = *reinterpret_cast<const u32x4*>(src);
+                if (cur.wrow0 + r < p.Lq)
+                    *reinterpret_cast<u32x4*>(og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
             }
-        if (hh == 0) { dst[D] = lam_out * kLn2; dst[D + 1] = 0.0f; }
+        } else if (cur.wrow0 + col < p.Lq) {
+            // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
+            float* dst = p.ws + ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + cur.wrow0 + col) *
+                                    (D + 2);
+#pragma unroll
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int dc = 32 * i + 8 * gq + 4 * hh;
+                    float4 x;
+                    x.x = g.U[i][4 * gq + 0] * fin; x.y = g.U[i][4 * gq + 1] * fin;
+                    x.z = g.U[i][4 * gq + 2] * fin; x.w = g.U[i][4 * gq + 3] * fin;
+                    *reinterpret_cast<float4*>(dst + dc) = x;
+                }
+            if (hh == 0) { dst[D] = lam_out * kLn2; dst[D + 1] = 0.0f; }
+        }
+        cur = nxt;
+        nvis = visible_count(p, cur.wrow0 + col);
     }
 }
 
-template <typename T, int D, int NW>
-static hipError_t launch_tile_nw(const Problem& p, bool online, hipStream_t st) {
-    const long m_tiles = (p.Lq + 32 * NW - 1) / (32 * NW);
-    const long total = m_tiles * p.splits * p.B * p.Hq;
+constexpr long kSlotsPerXcd = 64;     // 32 compute units x 2 resident workgroups
+
+static TileSched tile_sched(const Problem& p) {
+    const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
+    const long units = (long)p.splits * p.B * p.Hq;
+    TileSched sc;
+    // Pairing halves the number of workgroups; it pays once the unpaired launch would
+    // need at least two rounds of all workgroup slots.
+    sc.pair = (p.causal && m_tiles >= 2 && m_tiles * units >= 2 * 8 * kSlotsPerXcd) ? 1 : 0;
+    sc.wg_per_unit = (int)(sc.pair ? (m_tiles + 1) / 2 : m_tiles);
+    sc.nx = units % 8 == 0 ? 8 : 1;
+    const long nux = units / sc.nx;
+    // Paired workgroups all carry the same work: run as few units at a time as fill the
+    // XCD, so that their K/V stay in its L2.  Unpaired causal tiles differ in length: all
+    // units together, longest tiles first.
+    long group = nux;
+    if (sc.pair || !p.causal) group = std::max(1L, kSlotsPerXcd / sc.wg_per_unit);
+    sc.group = (int)std::min(group, nux);
+    return sc;
+}
+
+template <typename T, int D>
+static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
+    const TileSched sc = tile_sched(p);
+    const long total = (long)sc.wg_per_unit * p.splits * p.B * p.Hq;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     dim3 grid((unsigned)total);
     if (online)
-        hipLaunchKernelGGL((tile_kernel<T, D, true, NW>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((tile_kernel<T, D, true>), grid, dim3(kNW * 64), 0, st, p, sc);
     else
-        hipLaunchKernelGGL((tile_kernel<T, D, false, NW>), grid, dim3(NW * 64), 0, st, p);
+        hipLaunchKernelGGL((tile_kernel<T, D, false>), grid, dim3(kNW * 64), 0, st, p, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     return launch_merge_splits(p, st);
 }
 
-// Rows per workgroup: 256 (8 wavefronts) halves the K/V traffic into LDS per unit of work
-// and pays off once there are enough 256-row tiles to fill the chip; 128 otherwise.
-static int tile_rows(int B, int Hq, int Lq) {
-    static const int forced = [] {
-        const char* e = getenv("FLASHD_TILE_ROWS");
-        return e ? atoi(e) : 0;
-    }();
-    if (forced == 128 || forced == 256) return forced;
-    return 128;
-}
-
-template <typename T, int D>
-static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
-    if (tile_rows(p.B, p.Hq, p.Lq) == 256) return launch_tile_nw<T, D, 8>(p, online, st);
-    return launch_tile_nw<T, D, 4>(p, online, st);
-}
-
 long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d) {
     (void)Hkv; (void)d;
-    const int rows = tile_rows(B, Hq, Lq);
-    return (long)B * Hq * ((Lq + rows - 1) / rows);
+    return (long)B * Hq * ((Lq + 32 * kNW - 1) / (32 * kNW));
 }
 
 hipError_t launch_tile(const Problem& p, bool online, hipStream_t st) {
