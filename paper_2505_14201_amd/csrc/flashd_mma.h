@@ -14,6 +14,9 @@ namespace flashd {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -35,6 +38,9 @@ template <> struct Mma<BF16> {
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, bf16x8));
     }
+    static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
+        return __builtin_bit_cast(u32x2, __builtin_convertvector(x, bf16x4));
+    }
 };
 template <> struct Mma<F16> {
     static constexpr float kTheta = 14.0f;      // 2^14 is representable in fp16
@@ -44,6 +50,9 @@ template <> struct Mma<F16> {
     }
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, f16x8));
+    }
+    static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
+        return __builtin_bit_cast(u32x2, __builtin_convertvector(x, f16x4));
     }
 };
 

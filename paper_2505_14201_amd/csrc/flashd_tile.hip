@@ -266,37 +266,100 @@ __device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// How workgroup ids map to work (set by the launcher).
+// How workgroups map to work (set by the launcher).  The work is cut into "virtual
+// workgroups" (one row tile of a unit, or a long and a short one under a causal mask);
+// workgroup w of the launch runs the virtual workgroups w, w + gridDim.x, ... one after the
+// other, with the copy pipeline running on from one to the next.
 struct TileSched {
-    int pair;          // 1: a workgroup does row tiles (m_tiles - 1 - r) and r of its unit
-    int wg_per_unit;   // workgroups per (split, b, h) unit
+    int pair;          // 1: a virtual workgroup is row tiles (m_tiles - 1 - r) and r of its unit
+    int wg_per_unit;   // virtual workgroups per (split, b, h) unit
     int nx;            // 8: unit u runs on XCD u % 8 (ids go round-robin over the XCDs); 1: no such mapping
     int group;         // units of one XCD that are in flight together
+    int total;         // virtual workgroups
 };
 
-// One row tile of one unit as seen by a wavefront and by a lane.
-struct Item {                   // all members are wavefront-uniform
-    int m0, wrow0;              // first row of the workgroup / of the wavefront
+// One row tile of one unit as seen by a wavefront.  All members are wavefront-uniform.
+struct Item {
+    bool valid;
+    int sp, b, h;               // split, batch, query head
+    const uint16_t* qg;         // this head's Q, K, V, O
+    const uint16_t* kg;
+    const uint16_t* vg;
+    uint16_t* og;
+    int wrow0;                  // first row of the wavefront
     int wmax, wmin;             // most / fewest keys visible to a row of the wavefront
-    int n;                      // key tiles of this item (within the workgroup's split)
+    int n;                      // key tiles of this item (within its split)
     int jbase;                  // first key of tile 0
 };
 
+// Item number seq of this workgroup, or an invalid item when the workgroup has run out of
+// work.  (A virtual workgroup that is a pair whose two row tiles coincide has one item; the
+// caller skips the other.)
 template <int D>
-__device__ __forceinline__ Item make_item(const Problem& p, int mt, int sp, int wave) {
+__device__ __forceinline__ Item make_item(const Problem& p, const TileSched& sc, int seq,
+                                          int wave, bool& skip) {
     constexpr int kBM = 32 * kNW;
     Item it;
-    it.m0 = mt * kBM;
-    it.wrow0 = it.m0 + wave * 32;
+    it.valid = false;
+    it.n = 0;
+    skip = false;
+    const int ipv = sc.pair ? 2 : 1;
+    const int v = blockIdx.x + (seq / ipv) * gridDim.x;
+    if (v >= sc.total) return it;
+    // virtual workgroup id -> (unit, rank of the row tile within the unit)
+    const int m_tiles = (p.Lq + kBM - 1) / kBM;
+    const int n_bh = p.B * p.Hq;
+    const int xcd = v % sc.nx;
+    const int local = v / sc.nx;
+    const int nux = (n_bh * p.splits) / sc.nx;         // units on this XCD
+    const int gw = sc.group * sc.wg_per_unit;
+    const int grp = local / gw;
+    const int within = local % gw;
+    const int gsz = min(sc.group, nux - grp * sc.group);
+    const int rank = within / gsz;                      // slowest inside a group
+    const int unit = xcd + sc.nx * (grp * sc.group + within % gsz);
+    int mt;
+    if (sc.pair) {
+        // the longer row tile first
+        mt = (seq % ipv) == 0 ? m_tiles - 1 - rank : rank;
+        if ((seq % ipv) == 1 && m_tiles - 1 - rank == rank) { skip = true; return it; }
+    } else {
+        mt = p.causal ? m_tiles - 1 - rank : rank;
+    }
+    it.valid = true;
+    it.sp = unit / n_bh;
+    const int bh = unit % n_bh;
+    it.b = bh / p.Hq;
+    it.h = bh % p.Hq;
+    const int kvh = it.h / (p.Hq / p.Hkv);
+    it.qg = static_cast<const uint16_t*>(p.q) + ((size_t)it.b * p.Hq + it.h) * (size_t)p.Lq * D;
+    it.kg = static_cast<const uint16_t*>(p.k) + ((size_t)it.b * p.Hkv + kvh) * (size_t)p.Lk * D;
+    it.vg = static_cast<const uint16_t*>(p.v) + ((size_t)it.b * p.Hkv + kvh) * (size_t)p.Lk * D;
+    it.og = static_cast<uint16_t*>(p.o) + ((size_t)it.b * p.Hq + it.h) * (size_t)p.Lq * D;
+    const int m0 = mt * kBM;
+    it.wrow0 = m0 + wave * 32;
     it.wmax = it.wrow0 < p.Lq ? visible_count(p, min(it.wrow0 + 31, p.Lq - 1)) : 0;
     it.wmin = (it.wrow0 + 31 < p.Lq) ? visible_count(p, it.wrow0) : 0;
-    const int blk_nvis = visible_count(p, min(it.m0 + kBM - 1, p.Lq - 1));
+    const int blk_nvis = visible_count(p, min(m0 + kBM - 1, p.Lq - 1));
     const int tiles_all = (p.Lk + kBC - 1) / kBC;
     const int per_split = (tiles_all + p.splits - 1) / p.splits;
-    const int t_begin = sp * per_split;
+    const int t_begin = it.sp * per_split;
     const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
     it.n = max(t_end - t_begin, 0);
     it.jbase = t_begin * kBC;
+    return it;
+}
+
+// The first valid item at or after seq (seq is advanced to it), or an invalid one.
+template <int D>
+__device__ __forceinline__ Item next_item(const Problem& p, const TileSched& sc, int& seq,
+                                          int wave) {
+    bool skip;
+    Item it = make_item<D>(p, sc, seq, wave, skip);
+    if (skip) {
+        ++seq;
+        it = make_item<D>(p, sc, seq, wave, skip);
+    }
     return it;
 }
 
@@ -336,49 +399,14 @@ void tile_kernel(Problem p, TileSched sc) {
     const int col = lane & 31;
     const int hh = lane >> 5;
 
-    // workgroup id -> (unit, rank of the row tile within the unit)
-    const int m_tiles = (p.Lq + kBM - 1) / kBM;
-    const int n_bh = p.B * p.Hq;
-    const int xcd = blockIdx.x % sc.nx;
-    const int local = blockIdx.x / sc.nx;
-    const int nux = (n_bh * p.splits) / sc.nx;         // units on this XCD
-    const int gw = sc.group * sc.wg_per_unit;
-    const int grp = local / gw;
-    const int within = local % gw;
-    const int gsz = min(sc.group, nux - grp * sc.group);
-    const int rank = within / gsz;                      // slowest inside a group
-    const int unit = xcd + sc.nx * (grp * sc.group + within % gsz);
-    const int sp = unit / n_bh;
-    const int bh = unit % n_bh;
-    const int b = bh / p.Hq;
-    const int h = bh % p.Hq;
-    const int kvh = h / (p.Hq / p.Hkv);
-    // row tiles of this workgroup: the longest first
-    int mt_of[2];
-    int n_items = 1;
-    if (sc.pair) {
-        mt_of[0] = m_tiles - 1 - rank;
-        mt_of[1] = rank;
-        n_items = mt_of[0] != mt_of[1] ? 2 : 1;
-    } else {
-        mt_of[0] = p.causal ? m_tiles - 1 - rank : rank;
-        mt_of[1] = 0;
-    }
-
-    const uint16_t* qg = static_cast<const uint16_t*>(p.q) +
-                         ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
-    const uint16_t* kg = static_cast<const uint16_t*>(p.k) +
-                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
-    const uint16_t* vg = static_cast<const uint16_t*>(p.v) +
-                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
-    uint16_t* og = static_cast<uint16_t*>(p.o) + ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
-
     const DmaLane<D> dl(wave, lane);
-    Item cur = make_item<D>(p, mt_of[0], sp, wave);
+    int seq = 0;
+    Item cur = next_item<D>(p, sc, seq, wave);
+    if (!cur.valid) return;
     int nvis = visible_count(p, cur.wrow0 + col);      // keys visible to the lane's row
     bool have0 = false;          // tile 0 of the current item is in flight or has landed
     if (cur.n > 0) {
-        tile_copy<D>(kg, vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
+        tile_copy<D>(cur.kg, cur.vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
         have0 = true;
     }
 
@@ -399,16 +427,16 @@ void tile_kernel(Problem p, TileSched sc) {
         const int qr = min(cur.wrow0 + col, p.Lq - 1);
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
-            g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
+            g.qf[kk] =
+                *reinterpret_cast<const u32x4*>(cur.qg + (size_t)qr * D + 16 * kk + 8 * hh);
     }
 
     const float c_log2 = p.scale * kLog2e;        // scores are carried in log2 units
     const float ninf = -__builtin_inff();
 
-    for (int item = 0; item < n_items; ++item) {
-        Item nxt;
-        nxt.n = 0;
-        if (item + 1 < n_items) nxt = make_item<D>(p, mt_of[1], sp, wave);
+    for (bool first = true; cur.valid; first = false) {
+        ++seq;
+        const Item nxt = next_item<D>(p, sc, seq, wave);
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -418,8 +446,8 @@ void tile_kernel(Problem p, TileSched sc) {
         g.beta = 0.0f;
 
         if (!have0 && cur.n > 0)
-            tile_copy<D>(kg, vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
-        if (item == 0 || !have0) {
+            tile_copy<D>(cur.kg, cur.vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
+        if (first || !have0) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
@@ -436,9 +464,10 @@ void tile_kernel(Problem p, TileSched sc) {
             const int j0 = cur.jbase + t * kBC;
             uint16_t* kdst = lds + (PAR ^ 1) * kTile;
             if (t + 1 < cur.n) {
-                tile_copy<D>(kg, vg, j0 + kBC, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
+                tile_copy<D>(cur.kg, cur.vg, j0 + kBC, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
             } else if (PAR == 1 && nxt.n > 0) {
-                tile_copy<D>(kg, vg, nxt.jbase, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
+                tile_copy<D>(nxt.kg, nxt.vg, nxt.jbase, p.Lk, dl, wave, lane, kdst,
+                             kdst + 2 * kTile);
                 have0 = true;
             }
             if (j0 < cur.wmax)
@@ -453,11 +482,12 @@ void tile_kernel(Problem p, TileSched sc) {
         }
 
         // The next row tile's Q fragments: requested now, needed after the epilogue.
-        if (item + 1 < n_items) {
+        if (nxt.valid) {
             const int qr = min(nxt.wrow0 + col, p.Lq - 1);
 #pragma unroll
             for (int kk = 0; kk < NKK; ++kk)
-                g.qf[kk] = *reinterpret_cast<const u32x4*>(qg + (size_t)qr * D + 16 * kk + 8 * hh);
+                g.qf[kk] = *reinterpret_cast<const u32x4*>(nxt.qg + (size_t)qr * D + 16 * kk +
+                                                           8 * hh);
         }
 
         // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
@@ -492,19 +522,11 @@ void tile_kernel(Problem p, TileSched sc) {
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int dc = 32 * i + 8 * gq + 4 * hh;            // 4 consecutive columns
-                    uint16_t h4[4];
+                    f32x4 x4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if constexpr (std::is_same<T, BF16>::value)
-                            h4[e] = f32_to_bf16(g.U[i][4 * gq + e] * fin);
-                        else
-                            h4[e] = __builtin_bit_cast(
-                                uint16_t, static_cast<_Float16>(g.U[i][4 * gq + e] * fin));
-                    }
+                    for (int e = 0; e < 4; ++e) x4[e] = g.U[i][4 * gq + e] * fin;
+                    const u32x2 w2 = Mma<T>::pack4(x4);     // round to nearest even
                     const int chunk = (dc >> 3) ^ (col % C::CPR);
-                    u32x2 w2;
-                    w2[0] = (uint32_t)h4[0] | ((uint32_t)h4[1] << 16);
-                    w2[1] = (uint32_t)h4[2] | ((uint32_t)h4[3] << 16);
                     *reinterpret_cast<u32x2*>(&stage[srow * D + 8 * chunk + (dc & 4)]) = w2;
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -519,11 +541,12 @@ void tile_kernel(Problem p, TileSched sc) {
                                       (r & 15) * D + 8 * (c ^ (r % C::CPR));
                 const u32x4 x = *reinterpret_cast<const u32x4*>(src);
                 if (cur.wrow0 + r < p.Lq)
-                    *reinterpret_cast<u32x4*>(og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
+                    *reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
             }
         } else if (cur.wrow0 + col < p.Lq) {
             // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
-            float* dst = p.ws + ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + cur.wrow0 + col) *
+            float* dst = p.ws + ((((size_t)cur.sp * p.B + cur.b) * p.Hq + cur.h) * (size_t)p.Lq +
+                                 cur.wrow0 + col) *
                                     (D + 2);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
@@ -542,33 +565,55 @@ void tile_kernel(Problem p, TileSched sc) {
     }
 }
 
-constexpr long kSlotsPerXcd = 64;     // 32 compute units x 2 resident workgroups
+constexpr int kXcds = 8;
+constexpr int kCusPerXcd = 32;
 
-static TileSched tile_sched(const Problem& p) {
+// resident workgroups per compute unit of one kernel instantiation (asked once)
+template <typename K>
+static int resident_per_cu(K kernel) {
+    static const int n = [kernel] {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kNW * 64, 0) != hipSuccess ||
+            nb < 1)
+            nb = 1;
+        return nb;
+    }();
+    return n;
+}
+
+static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
     const long units = (long)p.splits * p.B * p.Hq;
     TileSched sc;
-    // Pairing halves the number of workgroups; it pays once the unpaired launch would
-    // need at least two rounds of all workgroup slots.
-    sc.pair = (p.causal && m_tiles >= 2 && m_tiles * units >= 2 * 8 * kSlotsPerXcd) ? 1 : 0;
+    // Pairing halves the number of virtual workgroups; it pays once there are at least
+    // two rounds of them for all workgroup slots.
+    sc.pair = (p.causal && m_tiles >= 2 && m_tiles * units >= 2L * kXcds * slots_per_xcd) ? 1 : 0;
     sc.wg_per_unit = (int)(sc.pair ? (m_tiles + 1) / 2 : m_tiles);
-    sc.nx = units % 8 == 0 ? 8 : 1;
+    sc.nx = units % kXcds == 0 ? kXcds : 1;
     const long nux = units / sc.nx;
-    // Paired workgroups all carry the same work: run as few units at a time as fill the
-    // XCD, so that their K/V stay in its L2.  Unpaired causal tiles differ in length: all
-    // units together, longest tiles first.
+    // Virtual workgroups that all carry the same work (paired, or no mask): run as few
+    // units at a time as fill the XCD, so that their K/V stay in its L2.  Unpaired causal
+    // tiles differ in length: all units together, longest tiles first.
     long group = nux;
-    if (sc.pair || !p.causal) group = std::max(1L, kSlotsPerXcd / sc.wg_per_unit);
+    if (sc.pair || !p.causal) group = std::max(1L, (long)slots_per_xcd / sc.wg_per_unit);
     sc.group = (int)std::min(group, nux);
+    sc.total = (int)(sc.wg_per_unit * units);
     return sc;
 }
 
 template <typename T, int D>
 static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
-    const TileSched sc = tile_sched(p);
-    const long total = (long)sc.wg_per_unit * p.splits * p.B * p.Hq;
-    if (total > 0x7fffffffL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)total);
+    const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
+    if (m_tiles * p.splits * p.B * p.Hq > 0x7fffffffL) return hipErrorInvalidValue;
+    const int per_cu = online ? resident_per_cu(tile_kernel<T, D, true>)
+                              : resident_per_cu(tile_kernel<T, D, false>);
+    const TileSched sc = tile_sched(p, per_cu * kCusPerXcd);
+    // One workgroup per virtual workgroup, handed out by the hardware as slots free up.
+    // (The kernel can also walk several virtual workgroups per workgroup, but a fixed split
+    // loses: of the two workgroups resident on a compute unit the older one is served first
+    // and runs a third faster, and only dynamic hand-out evens that out.)
+    const long wgs = sc.total;
+    dim3 grid((unsigned)wgs);
     if (online)
         hipLaunchKernelGGL((tile_kernel<T, D, true>), grid, dim3(kNW * 64), 0, st, p, sc);
     else

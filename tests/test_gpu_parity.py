@@ -256,3 +256,34 @@ def test_first_config_in_full():
     err = check(got, ref, torch.float32, "config 1")
     assert err <= 1e-5 * max(1.0, float(np.abs(ref).max()))
     assert math.isfinite(err)
+
+
+# Shapes with more row tiles than the GPU has workgroup slots: the tile kernel then walks
+# several row tiles per workgroup (under a causal mask a long and a short one as a pair,
+# with a lone middle tile when their number is odd) and orders them per XCD.  Checked on all
+# rows of a few heads plus sampled rows everywhere.
+#   (B, Hq, Hkv, Lq, Lk, d, dtype, causal)
+SCHEDULE_SHAPES = [
+    (2, 64, 64, 1152, 1152, 128, "bf16", True),     # 9 row tiles: pairs + middle tile
+    (2, 64, 16, 1100, 1300, 128, "f16", True),      # ragged, Lq != Lk, GQA
+    (1, 40, 40, 2048, 2048, 128, "bf16", False),    # no mask, units a multiple of 8
+    (1, 36, 12, 2000, 1000, 128, "bf16", False),    # units not a multiple of 8, ragged
+    (2, 64, 64, 2048, 2048, 64, "f16", True),       # d = 64: more resident workgroups
+    (1, 96, 96, 1280, 1280, 64, "bf16", False),
+]
+
+
+@pytest.mark.parametrize("shape", SCHEDULE_SHAPES)
+@pytest.mark.parametrize("variant", [TILE, ONLINE])
+def test_many_row_tiles_per_workgroup(shape, variant):
+    B, Hq, Hkv, Lq, Lk, d, dtype, causal = shape
+    w = synthetic.small("sched", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=7000 + Lq + Hq)
+    q, k, v, _ = synthetic.make_qkv(w)
+    got = run_flashd(q, k, v, causal, w.scale, variant, 1)
+    heads = [(0, 0), (B - 1, Hq - 1), (B // 2, Hq // 2 + 1)]
+    must = [(b, h, i) for (b, h) in heads for i in range(Lq)]
+    rows = synthetic.sample_rows(w, len(must) + 4096, seed=7001, must=must)
+    ref = oracle(q, k, v, causal, w.scale, rows)
+    idx = torch.from_numpy(rows.astype(np.int64))
+    sel = got[idx[:, 0], idx[:, 1], idx[:, 2], :]
+    check(sel, ref, DT[dtype], f"{shape} variant={variant}")
