@@ -237,16 +237,29 @@ __device__ __forceinline__ void phase_coeffs(const uint16_t* ks, const f32x16 (&
     }
 }
 
-// Phase 3: U <- U + P V   (O^T = V^T P^T)
-template <typename T, int D>
-__device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
-                                             const u32x4 (&bfrag)[4]) {
+// The first kAhead V operands of phase 3, requested before phase 2 so that they arrive
+// while the coefficients are computed.
+template <int D>
+__device__ __forceinline__ void prefetch_v(const uint16_t* vs, const TileRegs<D>& g,
+                                           u32x4 (&va)[kAhead]) {
     constexpr int NDB = D / 32;
-    constexpr int NV = 4 * NDB;           // V operands / output products per tile
-    u32x4 va[NV];
 #pragma unroll
     for (int m = 0; m < kAhead; ++m)
         va[m] = tile_v_operand<D>(vs, g.vaddr[m % NDB], 16 * (m / NDB));
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Phase 3: U <- U + P V   (O^T = V^T P^T); va0 = the operands prefetch_v() asked for.
+template <typename T, int D>
+__device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
+                                             const u32x4 (&bfrag)[4],
+                                             const u32x4 (&va0)[kAhead]) {
+    constexpr int NDB = D / 32;
+    constexpr int NV = 4 * NDB;           // V operands / output products per tile
+    static_assert(NV >= kAhead, "operand prefetch deeper than the phase");
+    u32x4 va[NV];
+#pragma unroll
+    for (int m = 0; m < kAhead; ++m) va[m] = va0[m];
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
         g.U[m % NDB] = Mma<T>::mfma(va[m], bfrag[m / NDB], g.U[m % NDB]);
@@ -254,7 +267,6 @@ __device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
             va[m + kAhead] =
                 tile_v_operand<D>(vs, g.vaddr[(m + kAhead) % NDB], 16 * ((m + kAhead) / NDB));
     }
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
     if (NV > kAhead) {
 #pragma unroll
         for (int m = 0; m < NV - kAhead; ++m) {
@@ -372,10 +384,17 @@ __device__ __forceinline__ void tile_math(const uint16_t* lds, TileRegs<D>& g, i
     constexpr int kTile = kBC * D;
     f32x16 acc[2];
     u32x4 bfrag[4];
+    // D = 128: the first V operands are requested before phase 2.  D = 64 asks for them at
+    // the start of phase 3 instead: the registers that early requests hold would cost it
+    // the third resident workgroup per compute unit.
+    constexpr bool kEarlyV = D == 128;
+    u32x4 va0[kAhead];
     phase_scores<T, D>(lds + PAR * kTile, g, acc);
+    if (kEarlyV) prefetch_v<D>(lds + (2 + PAR) * kTile, g, va0);
     phase_coeffs<T, D, ONLINE>(lds + PAR * kTile, acc, bfrag, g, j0, hh, lane, nvis, general,
                                c_log2);
-    phase_output<T, D>(lds + (2 + PAR) * kTile, g, bfrag);
+    if (!kEarlyV) prefetch_v<D>(lds + (2 + PAR) * kTile, g, va0);
+    phase_output<T, D>(lds + (2 + PAR) * kTile, g, bfrag, va0);
 }
 
 // 4 wavefronts of 32 query rows each per workgroup, two workgroups per compute unit.  K and
