@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # HBM-side bytes per launch of the dominant kernel, from the profiler's FETCH_SIZE and
 # WRITE_SIZE counters scaled by a 1 GiB device copy (the summaries under profiles/ give the
 # commands and the raw readings); they cannot be read from inside this process.
-TRAFFIC_PREFILL_BYTES = 738.2e6
+TRAFFIC_PREFILL_BYTES = 340.1e6
 TRAFFIC_DECODE_BYTES = 2150.8e6
 
 
