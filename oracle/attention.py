@@ -30,6 +30,11 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_long]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_skip_stats.restype = ctypes.c_int
+        lib.oracle_skip_stats.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float,
+            ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -69,3 +74,22 @@ def attn(q, k, v, causal: bool, scale: float, algo: str = "definition", rows=Non
     if rc != 0:
         raise ValueError("oracle_attn rejected its arguments")
     return out
+
+
+def skip_stats(q, k, causal: bool, scale: float, lo: float = -6.0, hi: float = 11.0):
+    """(steps, low, high) of the static skip rule of Sec. III-C over all query rows: steps
+    i >= 2 of each row's visible keys, those with s_i - s_{i-1} <= lo, those with >= hi.
+    Scores in the fixed fp32 arithmetic that skip_oracle.c documents."""
+    lib = _load()
+    qf, kf = _as_f32(q), _as_f32(k)
+    B, Hq, Lq, d = qf.shape
+    Bk, Hkv, Lk, dk = kf.shape
+    if Bk != B or dk != d:
+        raise ValueError("shape mismatch")
+    counts = np.zeros(3, dtype=np.uint64)
+    rc = lib.oracle_skip_stats(qf.ctypes.data, kf.ctypes.data, B, Hq, Hkv, Lq, Lk, d,
+                               int(bool(causal)), float(np.float32(scale)),
+                               float(np.float32(lo)), float(np.float32(hi)), counts.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_skip_stats rejected its arguments")
+    return int(counts[0]), int(counts[1]), int(counts[2])

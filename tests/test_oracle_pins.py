@@ -432,3 +432,90 @@ def test_storage_dtypes_are_widened_exactly():
 def test_skip_rule_counts():
     lo, hi, n = rec.skip_counts([0.0, -6.0, 5.0, 16.0, 15.0, 4.0, 4.0 - 5.99])
     assert (lo, hi, n) == (2, 2, 6)
+
+
+# ---- static skip statistics (Sec. III-C, Table I) --------------------------------------
+
+def _skip_brute(q, k, causal, scale, lo=-6.0, hi=11.0, margin=1e-3):
+    """Plain-Python count in fp64; also returns the smallest distance of a score difference
+    from a threshold (the fp32 oracle must agree exactly when that is not tiny)."""
+    q = q.double().numpy()
+    k = k.double().numpy()
+    B, Hq, Lq, d = q.shape
+    _, Hkv, Lk, _ = k.shape
+    steps = low = high = 0
+    closest = float("inf")
+    for b in range(B):
+        for h in range(Hq):
+            kh = k[b, h // (Hq // Hkv)]
+            for i in range(Lq):
+                nvis = min(max(i + (Lk - Lq) + 1, 0), Lk) if causal else Lk
+                s = (kh[:nvis] @ q[b, h, i]) * float(np.float32(scale))
+                dlt = np.diff(s)
+                steps += len(dlt)
+                low += int(np.sum(dlt <= lo))
+                high += int(np.sum(dlt >= hi))
+                if len(dlt):
+                    closest = min(closest, float(np.min(np.abs(dlt - lo))),
+                                  float(np.min(np.abs(dlt - hi))))
+    return steps, low, high, closest
+
+
+def test_skip_stats_worked_example_with_exact_scores():
+    # q = e_0, scale 1: the scores are the first components of the keys, all exact
+    vals = [0.0, -6.0, 5.0, 16.0, 15.0, 4.0, -2.0]     # differences -6, 11, 11, -1, -11, -6
+    k = torch.zeros(1, 1, len(vals), 4)
+    k[0, 0, :, 0] = torch.tensor(vals)
+    q = torch.zeros(1, 1, 1, 4)
+    q[0, 0, 0, 0] = 1.0
+    assert oa.skip_stats(q, k, False, 1.0) == (6, 3, 2)       # thresholds are inclusive
+    assert oa.skip_stats(q, k, False, 1.0, lo=-6.5, hi=11.5) == (6, 1, 0)
+    # causal, one query per key: row i walks keys 0..i
+    qc = q.expand(1, 1, len(vals), 4).contiguous()
+    dl = np.diff(vals)
+    exp = (sum(range(len(vals))), sum(int(np.sum(dl[:i] <= -6)) for i in range(len(vals))),
+           sum(int(np.sum(dl[:i] >= 11)) for i in range(len(vals))))
+    assert oa.skip_stats(qc, k, True, 1.0) == exp
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 9, 9, 16), (2, 4, 2, 5, 12, 8), (1, 3, 1, 12, 5, 32)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_skip_stats_match_brute_force(shape, causal):
+    B, Hq, Hkv, Lq, Lk, d = shape
+    rng = np.random.default_rng(99 + Lq)
+    q = torch.from_numpy((4 * rng.standard_normal((B, Hq, Lq, d))).astype(np.float32))
+    k = torch.from_numpy((4 * rng.standard_normal((B, Hkv, Lk, d))).astype(np.float32))
+    scale = 1.0 / math.sqrt(d)
+    steps, low, high, closest = _skip_brute(q, k, causal, scale)
+    assert closest > 1e-3          # no difference sits on a threshold: fp32 and fp64 must agree
+    assert low > 0 and high > 0    # the sample exercises both counters
+    assert oa.skip_stats(q, k, causal, scale) == (steps, low, high)
+    assert rec.skip_counts is not None
+
+
+def test_skip_stats_rate_has_the_gaussian_closed_form():
+    # q = a e_0 and iid N(0,1) first key components: s_j is N(0, sigma^2) with sigma = a * scale,
+    # a step's difference N(0, 2 sigma^2), so P(low) = Phi(-6 / (sigma sqrt 2)) and
+    # P(high) = Phi(-11 / (sigma sqrt 2)).
+    rng = np.random.default_rng(5)
+    n = 200001
+    k = torch.zeros(1, 1, n, 2)
+    k[0, 0, :, 0] = torch.from_numpy(rng.standard_normal(n).astype(np.float32))
+    q = torch.tensor([[[[8.0, 0.0]]]])
+    sigma = 8.0 * 0.5
+    steps, low, high = oa.skip_stats(q, k, False, 0.5)
+    p_low = 0.5 * math.erfc(6.0 / (sigma * math.sqrt(2.0)) / math.sqrt(2.0))
+    p_high = 0.5 * math.erfc(11.0 / (sigma * math.sqrt(2.0)) / math.sqrt(2.0))
+    assert steps == n - 1
+    # neighbouring steps share a score, which at most doubles the binomial variance
+    for cnt, pr in ((low, p_low), (high, p_high)):
+        sd = math.sqrt(2.0 * steps * pr * (1.0 - pr))
+        assert abs(cnt - steps * pr) < 5.0 * sd, (cnt, steps * pr, sd)
+
+
+def test_skip_stats_storage_types_are_widened_exactly():
+    rng = np.random.default_rng(6)
+    for dt in (torch.bfloat16, torch.float16):
+        q = torch.from_numpy((3 * rng.standard_normal((1, 2, 6, 16))).astype(np.float32)).to(dt)
+        k = torch.from_numpy((3 * rng.standard_normal((1, 1, 40, 16))).astype(np.float32)).to(dt)
+        assert oa.skip_stats(q, k, False, 0.25) == oa.skip_stats(q.float(), k.float(), False, 0.25)
