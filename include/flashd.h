@@ -103,6 +103,23 @@ size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int
 /* The number of splits the automatic choice takes for this problem (>= 1). */
 int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant);
 
+/*
+ * Static skip statistics (Sec. III-C; the quantity reported in Table I).  Over every query
+ * row and every step i >= 2 of Alg. 3 on that row's visible keys (same layout, head mapping
+ * and causal rule as above; v is not needed), counts
+ *     counts[0] = steps,
+ *     counts[1] = steps with s_i - s_{i-1} <= lo   (weight ~ 0, the step could be skipped),
+ *     counts[2] = steps with s_i - s_{i-1} >= hi   (weight ~ 1, the output becomes v_i).
+ * The paper's static range is lo = -6, hi = 11.  Score arithmetic (fixed, so that the counts
+ * are reproducible bit for bit): acc = fma(q[t], k[t], acc) over t = 0 .. d-1 in fp32,
+ * s = acc * scale, the difference in fp32.
+ * counts: DEVICE pointer to three 64-bit unsigned integers, 8-byte aligned, overwritten by
+ * the enqueued work.  Errors as for flashd_attn_fwd.  Never allocates.
+ */
+int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                      int causal, float scale, int dtype, float lo, float hi,
+                      unsigned long long* counts, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* flashd_status_string(int status);
 

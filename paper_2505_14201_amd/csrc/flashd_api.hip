@@ -178,6 +178,29 @@ int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int
                false);
 }
 
+int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                      int causal, float scale, int dtype, float lo, float hi,
+                      unsigned long long* counts, void* stream) {
+    if (!q || !k || !counts) return FLASHD_E_NULL;
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    int rc = validate_shape(s);
+    if (rc != FLASHD_OK) return rc;
+    if (((uintptr_t)q | (uintptr_t)k) & 15u) return FLASHD_E_ALIGN;
+    if ((uintptr_t)counts & 7u) return FLASHD_E_ALIGN;
+    rc = check_arch();
+    if (rc != FLASHD_OK) return rc;
+    Problem p;
+    p.q = q; p.k = k; p.v = nullptr; p.o = nullptr; p.ws = nullptr;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Lq = Lq; p.Lk = Lk; p.d = d;
+    p.dtype = dtype;
+    p.causal = causal != 0;
+    p.splits = 1;
+    p.scale = scale;
+    const hipError_t e =
+        flashd::launch_skip_stats(p, lo, hi, counts, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;
+}
+
 int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant) {
     const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
     if (validate_shape(s) != FLASHD_OK) return 1;

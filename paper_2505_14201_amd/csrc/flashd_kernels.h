@@ -27,4 +27,9 @@ hipError_t launch_decode(const Problem& p, bool online, hipStream_t st);
 bool decode_applies(int Hq, int Hkv, int Lq);
 long decode_workgroups(int B, int Hkv);
 
+// Static skip statistics of Sec. III-C: counts[0..2] = steps, steps with a score difference
+// <= lo, steps with one >= hi (overwritten).  Uses p.q, p.k and the shape only.
+hipError_t launch_skip_stats(const Problem& p, float lo, float hi, unsigned long long* counts,
+                             hipStream_t st);
+
 }  // namespace flashd

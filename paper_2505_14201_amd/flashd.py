@@ -22,7 +22,7 @@ MAX_SPLITS = 64
 _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
-           "flashd_auto_splits", "flashd_status_string", "flashd_version")
+           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats")
 
 
 class FlashdError(RuntimeError):
@@ -47,6 +47,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_workspace_bytes.argtypes = [i] * 9
     lib.flashd_auto_splits.restype = i
     lib.flashd_auto_splits.argtypes = [i] * 8
+    lib.flashd_skip_stats.restype = i
+    lib.flashd_skip_stats.argtypes = [p, p, i, i, i, i, i, i, i, f, i, f, f, p, p]
     lib.flashd_status_string.restype = ctypes.c_char_p
     lib.flashd_status_string.argtypes = [i]
     lib.flashd_version.restype = i
@@ -128,3 +130,34 @@ def attn_fwd_ex(q, k, v, o, causal: bool, scale: float, variant: int = VARIANT_A
                                      st, int(variant), int(splits), ws_ptr, ws_bytes)
     if rc != 0:
         raise FlashdError(rc)
+
+
+def skip_stats(q, k, causal: bool, scale: float, lo: float = -6.0, hi: float = 11.0,
+               counts=None, stream=None):
+    """flashd_skip_stats: (steps, low, high) of the static skip rule.  `counts`: optional
+    GPU int64 tensor of 3 elements to receive the result (then nothing is read back and the
+    call only enqueues work); otherwise a tensor is created and the counts are returned."""
+    if not (q.is_cuda and k.is_cuda and q.is_contiguous() and k.is_contiguous()):
+        raise ValueError("q and k must be contiguous GPU tensors")
+    if q.dtype not in _DTYPE or k.dtype != q.dtype or q.dim() != 4 or k.dim() != 4:
+        raise ValueError("expected q: [B,Hq,Lq,d] and k: [B,Hkv,Lk,d] of one storage type")
+    B, Hq, Lq, d = q.shape
+    Bk, Hkv, Lk, dk = k.shape
+    if Bk != B or dk != d:
+        raise ValueError("batch or head dimension mismatch between q and k")
+    own = counts is None
+    with torch.cuda.device(q.device):
+        if own:
+            counts = torch.empty(3, dtype=torch.int64, device=q.device)
+        elif not (counts.is_cuda and counts.dtype == torch.int64 and counts.numel() >= 3
+                  and counts.is_contiguous()):
+            raise ValueError("counts must be a contiguous GPU int64 tensor of 3 elements")
+        rc = _lib.flashd_skip_stats(q.data_ptr(), k.data_ptr(), B, Hq, Hkv, Lq, Lk, d,
+                                    int(bool(causal)), float(scale), _DTYPE[q.dtype], float(lo),
+                                    float(hi), counts.data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise FlashdError(rc)
+    if not own:
+        return None
+    c = counts.cpu()
+    return int(c[0]), int(c[1]), int(c[2])

@@ -131,3 +131,20 @@ def test_binding_rejects_cpu_tensors():
     q = torch.zeros(1, 1, 4, 64)
     with pytest.raises(ValueError):
         flashd.attn_fwd(q, q, q, q, False, 1.0)
+
+
+def stats(q=P, k=P, counts=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=512, d=64, dtype=flashd.BF16):
+    return flashd.raw().flashd_skip_stats(q, k, B, Hq, Hkv, Lq, Lk, d, 0, 1.0, dtype, -6.0, 11.0,
+                                          counts, None)
+
+
+def test_skip_stats_argument_errors():
+    for name in ("q", "k", "counts"):
+        assert stats(**{name: None}) == E_NULL
+    assert stats(Lk=0) == E_SHAPE
+    assert stats(dtype=7) == E_DTYPE
+    assert stats(d=80) == E_HEADDIM
+    assert stats(Hq=5) == E_GQA
+    assert stats(q=P + 8) == E_ALIGN
+    assert stats(counts=P + 4) == E_ALIGN
+    assert stats(counts=P + 8) != E_ALIGN          # 8-byte alignment is enough for the counters
