@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
     ap.add_argument("--no-ablation", action="store_true")
+    ap.add_argument("--no-skip-stats", action="store_true",
+                    help="skip the static skip-range statistics (Sec. III-C) of two workloads")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 1 GiB, 10 times (reference for "
                          "scaling the profiler's HBM byte counters)")
@@ -141,6 +143,21 @@ def main() -> int:
         out["ablation_online_softmax"] = {
             "kernel_ms": round(ev_abl / args.steps, 4),
             "TFLOP/s": round(flops / (ev_abl / args.steps * 1e-3) / 1e12, 2)}
+
+    if not args.no_skip_stats:
+        # Sec. III-C / Table I on synthetic inputs: share of Alg. 3 steps whose score
+        # difference leaves the static range [-6, 11]
+        def rates(wl, qg, kg):
+            cnt = torch.empty(3, dtype=torch.int64, device="cuda")
+            flashd.skip_stats(qg, kg, wl.causal, wl.scale, counts=cnt)       # warm-up
+            _, ms = time_calls(lambda _i: flashd.skip_stats(qg, kg, wl.causal, wl.scale,
+                                                            counts=cnt), 3, 0, 1)
+            steps, low, high = (int(x) for x in cnt.cpu())
+            return {"workload": wl.name, "steps": steps, "low_frac": round(low / steps, 6),
+                    "high_frac": round(high / steps, 6), "kernel_ms": round(ms / 3, 3)}
+        ws = synthetic.CONFIGS[4]
+        qs_, ks_, _, _ = synthetic.make_qkv(ws)
+        out["skip_stats"] = [rates(w, sets[0][0], sets[0][1]), rates(ws, qs_.cuda(), ks_.cuda())]
 
     del sets
     torch.cuda.empty_cache()

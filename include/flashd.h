@@ -104,6 +104,29 @@ size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int
 int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant);
 
 /*
+ * Attention forward over one chunk of keys with the state of Alg. 3 handed in and out
+ * (Sec. III-C: the state after a run of keys is (o, s_last, ln w_last), and only
+ * s_last - ln w_last enters later steps).  Processes this call's Lk keys after the keys
+ * that state_in stands for; chunked prefill, appended KV blocks and merging the results of
+ * key ranges held by different devices are all sequences of such calls.
+ *   state_in   DEVICE pointer or NULL (no earlier keys): [B][Hq][Lq][d + 2] fp32, per query
+ *              row (o[0..d), s, ln w).  A row that has seen no key has s = -inf, ln w = 0.
+ *   state_out  DEVICE pointer or NULL: same layout, receives the state after this call's keys,
+ *              normalised to (o, s = s_last - ln w_last, ln w = 0).  May equal state_in.
+ *   o          DEVICE pointer or NULL: the attention output after this call's keys in the
+ *              storage type (what the state's o holds).  o and state_out must not both be NULL.
+ *   causal_shift  with causal != 0, key j of THIS call is visible to query i iff
+ *              j <= i + causal_shift; for a chunk that starts at key offset k0 of Lk_total
+ *              keys that is (Lk_total - Lq) - k0.  Ignored when causal == 0.
+ * Other arguments, conventions and errors as for flashd_attn_fwd (all pointers 16-byte aligned).
+ * Takes scratch memory for partial states from the same grow-only cache as flashd_attn_fwd.
+ */
+int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
+                          const float* state_in, float* state_out,
+                          int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                          int causal, int causal_shift, float scale, int dtype, void* stream);
+
+/*
  * Static skip statistics (Sec. III-C; the quantity reported in Table I).  Over every query
  * row and every step i >= 2 of Alg. 3 on that row's visible keys (same layout, head mapping
  * and causal rule as above; v is not needed), counts

@@ -30,6 +30,11 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_long]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_attn_state.restype = ctypes.c_int
+        lib.oracle_attn_state.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, ctypes.c_int, ctypes.c_float]
         lib.oracle_skip_stats.restype = ctypes.c_int
         lib.oracle_skip_stats.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -93,3 +98,29 @@ def skip_stats(q, k, causal: bool, scale: float, lo: float = -6.0, hi: float = 1
     if rc != 0:
         raise ValueError("oracle_skip_stats rejected its arguments")
     return int(counts[0]), int(counts[1]), int(counts[2])
+
+
+def attn_state(q, k, v, causal: bool, scale: float, state_in=None, shift=None) -> np.ndarray:
+    """Alg. 3 over this call's keys, continuing from `state_in` (fp64 array [B,Hq,Lq,d+2] of
+    (o, s_last, ln w_last) per row, or None).  Returns the literal state in the same layout.
+    causal: key j visible to query i iff j <= i + shift (default Lk - Lq)."""
+    lib = _load()
+    qf, kf, vf = _as_f32(q), _as_f32(k), _as_f32(v)
+    B, Hq, Lq, d = qf.shape
+    Bk, Hkv, Lk, dk = kf.shape
+    if vf.shape != kf.shape or Bk != B or dk != d:
+        raise ValueError("shape mismatch")
+    out = np.empty((B, Hq, Lq, d + 2), dtype=np.float64)
+    sin_p = None
+    if state_in is not None:
+        state_in = np.ascontiguousarray(state_in, dtype=np.float64)
+        if state_in.shape != out.shape:
+            raise ValueError("state_in must be [B,Hq,Lq,d+2]")
+        sin_p = state_in.ctypes.data
+    sh = Lk - Lq if shift is None else int(shift)
+    rc = lib.oracle_attn_state(qf.ctypes.data, kf.ctypes.data, vf.ctypes.data, sin_p,
+                               out.ctypes.data, B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), sh,
+                               float(np.float32(scale)))
+    if rc != 0:
+        raise ValueError("oracle_attn_state rejected its arguments")
+    return out

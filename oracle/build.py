@@ -5,7 +5,8 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, "attn_oracle.c"), os.path.join(HERE, "skip_oracle.c")]
+SRCS = [os.path.join(HERE, "attn_oracle.c"), os.path.join(HERE, "skip_oracle.c"),
+        os.path.join(HERE, "state_oracle.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 

@@ -63,10 +63,12 @@ int auto_splits(const Shape& s, int variant) {
     return (int)sp;
 }
 
-size_t ws_bytes(const Shape& s, int splits) {
-    if (splits <= 1) return 0;
-    return (size_t)splits * s.B * s.Hq * s.Lq * (size_t)(s.d + 2) * sizeof(float);
+// n partial states (o[d], s, ln w) per query row
+size_t partial_bytes(const Shape& s, int n) {
+    return (size_t)n * s.B * s.Hq * s.Lq * (size_t)(s.d + 2) * sizeof(float);
 }
+
+size_t ws_bytes(const Shape& s, int splits) { return splits <= 1 ? 0 : partial_bytes(s, splits); }
 
 // ---- device check ----------------------------------------------------------
 
@@ -117,20 +119,31 @@ int cached_workspace(void* stream, size_t bytes, void** out) {
 
 // ---- common front end --------------------------------------------------------
 
+struct StateArgs {
+    bool on = false;                 // the state entry point: o may be NULL, shift is explicit
+    int shift = 0;
+    const float* in = nullptr;
+    float* out = nullptr;
+};
+
 int run(const void* q, const void* k, const void* v, void* o, const Shape& s, int causal,
         float scale, void* stream, int variant, int splits, void* workspace,
-        size_t workspace_bytes, bool use_cache) {
-    if (!q || !k || !v || !o) return FLASHD_E_NULL;
+        size_t workspace_bytes, bool use_cache, const StateArgs& sa = StateArgs()) {
+    if (!q || !k || !v) return FLASHD_E_NULL;
+    if (!o && !(sa.on && sa.out)) return FLASHD_E_NULL;
     int rc = validate_shape(s);
     if (rc != FLASHD_OK) return rc;
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o |
-                           (uintptr_t)workspace;
+                           (uintptr_t)workspace | (uintptr_t)sa.in | (uintptr_t)sa.out;
     if (bits & 15u) return FLASHD_E_ALIGN;
     const int var = resolve_variant(s, variant);
     if (var < 0) return FLASHD_E_VARIANT;
     if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
     const int sp = splits == 0 ? auto_splits(s, var) : splits;
-    const size_t need = ws_bytes(s, sp);
+    // The state entry point always goes through partial states; a single partial may be
+    // written straight into the caller's state buffer.
+    const bool direct = sa.on && sp == 1 && sa.out != nullptr;
+    const size_t need = sa.on ? (direct ? 0 : partial_bytes(s, sp)) : ws_bytes(s, sp);
     if (!use_cache && need > 0 && (workspace == nullptr || workspace_bytes < need))
         return FLASHD_E_WORKSPACE;
 
@@ -150,6 +163,11 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.causal = causal != 0;
     p.splits = sp;
     p.scale = scale;
+    p.shift = sa.on ? sa.shift : s.Lk - s.Lq;
+    p.partial = (sp > 1 || sa.on) ? 1 : 0;
+    p.state_in = sa.in;
+    p.state_out = sa.out;
+    if (direct) p.ws = sa.out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     const bool online = var == FLASHD_VARIANT_ONLINE_SOFTMAX;
@@ -178,6 +196,19 @@ int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int
                false);
 }
 
+int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
+                          const float* state_in, float* state_out, int B, int Hq, int Hkv, int Lq,
+                          int Lk, int d, int causal, int causal_shift, float scale, int dtype,
+                          void* stream) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    StateArgs sa;
+    sa.on = true;
+    sa.shift = causal_shift;
+    sa.in = state_in;
+    sa.out = state_out;
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true, sa);
+}
+
 int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
                       int causal, float scale, int dtype, float lo, float hi,
                       unsigned long long* counts, void* stream) {
@@ -196,6 +227,10 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.causal = causal != 0;
     p.splits = 1;
     p.scale = scale;
+    p.shift = Lk - Lq;
+    p.partial = 0;
+    p.state_in = nullptr;
+    p.state_out = nullptr;
     const hipError_t e =
         flashd::launch_skip_stats(p, lo, hi, counts, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;

@@ -20,6 +20,10 @@ struct Problem {
     int causal;         // 0/1
     int splits;         // >= 1
     float scale;
+    int shift;          // causal: key j is visible to query i iff j <= i + shift
+    int partial;        // 1: the main kernel writes partial states to ws (always with splits > 1)
+    const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32
+    float* state_out;        // optional state after this call's keys, same layout
 };
 
 // ---- storage types -------------------------------------------------------

@@ -207,7 +207,7 @@ void decode_kernel(Problem p) {
         const int hq = kvh * g + row / p.Lq;
         const int i = row % p.Lq;
         const size_t orow = ((size_t)b * p.Hq + hq) * (size_t)p.Lq + i;
-        if (p.splits == 1) {
+        if (!p.partial) {
             Store<T>::store(p.o, orow * D + t, o);
         } else {
             float* dst = p.ws + ((size_t)sp * p.B * p.Hq * p.Lq + orow) * (D + 2);
@@ -225,7 +225,7 @@ static hipError_t launch_decode_t(const Problem& p, bool online, hipStream_t st)
     else
         hipLaunchKernelGGL((decode_kernel<T, D, false>), grid, dim3(kDecThreads), 0, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.splits == 1) return e;
+    if (e != hipSuccess || !p.partial) return e;
     return launch_merge_splits(p, st);
 }
 

@@ -400,7 +400,7 @@ __device__ __forceinline__ void row_finish(float lam, float beta, float& fin, fl
 __device__ __forceinline__ int visible_count(const Problem& p, int i) {
     if (i >= p.Lq) return 0;
     if (!p.causal) return p.Lk;
-    return min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
+    return min(max(i + p.shift + 1, 0), p.Lk);
 }
 
 }  // namespace flashd

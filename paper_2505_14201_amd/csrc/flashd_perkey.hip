@@ -56,7 +56,7 @@ void perkey_kernel(Problem p) {
     for (int r = 0; r < R; ++r) {
         const int i = i0 + r;
         int n = p.Lk;
-        if (p.causal) n = min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
+        if (p.causal) n = min(max(i + p.shift + 1, 0), p.Lk);
         if (i >= p.Lq) n = 0;
         nvis[r] = min(n, k1);
         kend = max(kend, nvis[r]);
@@ -141,7 +141,7 @@ void perkey_kernel(Problem p) {
             for (int t = 0; t < D; ++t) qs[r][t] = o[r][t];
         }
         __builtin_amdgcn_wave_barrier();
-        if (p.splits == 1) {
+        if (!p.partial) {
             const size_t obase = qbase + (size_t)i * D;
             for (int t = lane; t < D; t += kWave) Store<T>::store(p.o, obase + t, qs[r][t]);
         } else {
@@ -153,7 +153,10 @@ void perkey_kernel(Problem p) {
     }
 }
 
-// Fold the split partials of each query row left to right with the sigmoid rule.
+// Fold the split partials of each query row left to right with the sigmoid rule, after the
+// state of earlier keys if one is given (p.state_in).  Writes the output (p.o, if not null)
+// and the state (p.state_out, if not null) as the run seen as one key: (o, s = Lam, ln w = 0).
+// state_out may be the buffer the single partial came from (same row, read before written).
 template <typename T, int D>
 __global__ __launch_bounds__(256)
 void merge_splits_kernel(Problem p) {
@@ -165,6 +168,14 @@ void merge_splits_kernel(Problem p) {
     if (row >= rows) return;
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     float lam = -__builtin_inff();
+    if (p.state_in) {
+        const float* src = p.state_in + row * (D + 2);
+        lam = src[D] - src[D + 1];
+        if (lam != -__builtin_inff()) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = src[c * 4 + t];
+        }
+    }
     for (int sp = 0; sp < p.splits; ++sp) {
         const float* src = p.ws + ((size_t)sp * rows + row) * (D + 2);
         const float lam_b = src[D] - src[D + 1];   // s - ln w
@@ -176,8 +187,16 @@ void merge_splits_kernel(Problem p) {
             for (int t = 0; t < 4; ++t) acc[t] = fmaf(src[c * 4 + t] - acc[t], W, acc[t]);
         }
     }
+    if (p.o) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) Store<T>::store(p.o, row * D + c * 4 + t, acc[t]);
+        for (int t = 0; t < 4; ++t) Store<T>::store(p.o, row * D + c * 4 + t, acc[t]);
+    }
+    if (p.state_out) {
+        float* dst = p.state_out + row * (D + 2);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dst[c * 4 + t] = acc[t];
+        if (c == 0) { dst[D] = lam; dst[D + 1] = 0.0f; }
+    }
 }
 
 template <typename T, int D>
@@ -195,7 +214,7 @@ static hipError_t launch_perkey_t(const Problem& p, hipStream_t st) {
     dim3 grid((unsigned)(row_blocks * p.splits), (unsigned)p.Hq, (unsigned)p.B);
     hipLaunchKernelGGL((perkey_kernel<T, D>), grid, dim3(kPerKeyWaves * kWave), 0, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.splits == 1) return e;
+    if (e != hipSuccess || !p.partial) return e;
     return launch_merge_t<T, D>(p, st);
 }
 

@@ -48,7 +48,7 @@ void skip_stats_kernel(Problem p, float lo, float hi, unsigned long long* counts
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         int nvis = p.Lk;
-        if (p.causal) nvis = min(max(i + (p.Lk - p.Lq) + 1, 0), p.Lk);
+        if (p.causal) nvis = min(max(i + p.shift + 1, 0), p.Lk);
         float carry = 0.0f;                               // score of key j0 - 1
         for (int j0 = 0; j0 < nvis; j0 += 64) {
             const int j = j0 + lane;

@@ -524,7 +524,7 @@ void tile_kernel(Problem p, TileSched sc) {
         asm volatile("" : "+v"(elane));
         const int col = elane & 31;
         const int hh = elane >> 5;
-        if (p.splits == 1) {
+        if (!p.partial) {
             // Stage the wavefront's 32 x D output block through LDS so that the global
             // stores are 16 bytes per lane and whole rows are contiguous.  Slot 1 is idle
             // after the last barrier and never the target of the copy of the next row
@@ -638,7 +638,7 @@ static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
     else
         hipLaunchKernelGGL((tile_kernel<T, D, false>), grid, dim3(kNW * 64), 0, st, p, sc);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.splits == 1) return e;
+    if (e != hipSuccess || !p.partial) return e;
     return launch_merge_splits(p, st);
 }
 

@@ -22,7 +22,7 @@ MAX_SPLITS = 64
 _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
-           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats")
+           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state")
 
 
 class FlashdError(RuntimeError):
@@ -47,6 +47,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_workspace_bytes.argtypes = [i] * 9
     lib.flashd_auto_splits.restype = i
     lib.flashd_auto_splits.argtypes = [i] * 8
+    lib.flashd_attn_fwd_state.restype = i
+    lib.flashd_attn_fwd_state.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, f, i, p]
     lib.flashd_skip_stats.restype = i
     lib.flashd_skip_stats.argtypes = [p, p, i, i, i, i, i, i, i, f, i, f, f, p, p]
     lib.flashd_status_string.restype = ctypes.c_char_p
@@ -161,3 +163,34 @@ def skip_stats(q, k, causal: bool, scale: float, lo: float = -6.0, hi: float = 1
         return None
     c = counts.cpu()
     return int(c[0]), int(c[1]), int(c[2])
+
+
+def attn_fwd_state(q, k, v, causal: bool, scale: float, o=None, state_in=None, state_out=None,
+                   causal_shift=None, stream=None) -> None:
+    """flashd_attn_fwd_state: one chunk of keys with the Alg. 3 state handed in and out.
+    States are float32 GPU tensors [B, Hq, Lq, d + 2]; causal_shift defaults to Lk - Lq."""
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if q.dtype not in _DTYPE or not (k.dtype == v.dtype == q.dtype):
+        raise ValueError("q, k, v must share one of float32/float16/bfloat16")
+    B, Hq, Lq, d = q.shape
+    Bk, Hkv, Lk, dk = k.shape
+    if Bk != B or dk != d or v.shape != k.shape:
+        raise ValueError("shape mismatch between q, k and v")
+    if o is not None and (o.shape != q.shape or o.dtype != q.dtype or not o.is_cuda
+                          or not o.is_contiguous()):
+        raise ValueError("o must match q")
+    for name, t in (("state_in", state_in), ("state_out", state_out)):
+        if t is not None and (tuple(t.shape) != (B, Hq, Lq, d + 2) or t.dtype != torch.float32
+                              or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous float32 GPU tensor [B, Hq, Lq, d + 2]")
+    shift = Lk - Lq if causal_shift is None else int(causal_shift)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    with torch.cuda.device(q.device):
+        rc = _lib.flashd_attn_fwd_state(q.data_ptr(), k.data_ptr(), v.data_ptr(), ptr(o),
+                                        ptr(state_in), ptr(state_out), B, Hq, Hkv, Lq, Lk, d,
+                                        int(bool(causal)), shift, float(scale), _DTYPE[q.dtype],
+                                        _stream_ptr(stream))
+    if rc != 0:
+        raise FlashdError(rc)

@@ -519,3 +519,77 @@ def test_skip_stats_storage_types_are_widened_exactly():
         q = torch.from_numpy((3 * rng.standard_normal((1, 2, 6, 16))).astype(np.float32)).to(dt)
         k = torch.from_numpy((3 * rng.standard_normal((1, 1, 40, 16))).astype(np.float32)).to(dt)
         assert oa.skip_stats(q, k, False, 0.25) == oa.skip_stats(q.float(), k.float(), False, 0.25)
+
+
+# ---- Alg. 3 with the state handed in and out (Sec. III-C) ------------------------------
+
+def _rand_qkv(rng, B, Hq, Hkv, Lq, Lk, d, std=1.0):
+    mk = lambda *s: torch.from_numpy((std * rng.standard_normal(s)).astype(np.float32))
+    return mk(B, Hq, Lq, d), mk(B, Hkv, Lk, d), mk(B, Hkv, Lk, d)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_state_of_a_run_is_output_and_log_sum_exp(causal):
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, Lq, Lk, d = 2, 4, 2, 7, 19, 8
+    q, k, v = _rand_qkv(rng, B, Hq, Hkv, Lq, Lk, d, 2.0)
+    st = oa.attn_state(q, k, v, causal, 0.3)
+    ref = oa.attn(q, k, v, causal, 0.3)
+    assert np.allclose(st[..., :d], ref, rtol=0, atol=1e-12)
+    # s_last - ln w_last = ln sum_j e^{s_j} over the visible keys (weight equation, Sec. III-B)
+    kk = k.double().repeat_interleave(Hq // Hkv, dim=1)
+    s = (q.double() @ kk.transpose(-1, -2)).numpy() * float(np.float32(0.3))
+    for i in range(Lq):
+        nvis = min(i + (Lk - Lq) + 1, Lk) if causal else Lk
+        lse = scipy.special.logsumexp(s[:, :, i, :nvis], axis=-1)
+        assert np.allclose(st[:, :, i, d] - st[:, :, i, d + 1], lse, rtol=0, atol=1e-12)
+        assert np.allclose(st[:, :, i, d], s[:, :, i, nvis - 1])         # s_last is literal
+
+
+@pytest.mark.parametrize("cuts", [(5,), (1, 2), (7, 8, 18)])
+def test_chunked_keys_with_state_passing_equal_one_pass(cuts):
+    rng = np.random.default_rng(12)
+    B, Hq, Hkv, Lq, Lk, d = 1, 2, 1, 6, 19, 4
+    q, k, v = _rand_qkv(rng, B, Hq, Hkv, Lq, Lk, d, 3.0)
+    for causal in (False, True):
+        full = oa.attn_state(q, k, v, causal, 0.5)
+        st, k0 = None, 0
+        for k1 in list(cuts) + [Lk]:
+            st = oa.attn_state(q, k[:, :, k0:k1].contiguous(), v[:, :, k0:k1].contiguous(), causal,
+                               0.5, st, shift=(Lk - Lq) - k0)
+            k0 = k1
+        # the literal recurrence does the same steps in the same order either way
+        assert np.allclose(st, full, rtol=0, atol=1e-13)
+
+
+def test_state_in_only_enters_through_s_minus_ln_w():
+    rng = np.random.default_rng(13)
+    q, k, v = _rand_qkv(rng, 1, 1, 1, 3, 9, 4, 2.0)
+    first = oa.attn_state(q, k[:, :, :4].contiguous(), v[:, :, :4].contiguous(), False, 1.0)
+    moved = first.copy()
+    moved[..., 4] += 0.75                      # (s, ln w) -> (s + delta, ln w + delta)
+    moved[..., 5] += 0.75
+    a = oa.attn_state(q, k[:, :, 4:].contiguous(), v[:, :, 4:].contiguous(), False, 1.0, first)
+    b = oa.attn_state(q, k[:, :, 4:].contiguous(), v[:, :, 4:].contiguous(), False, 1.0, moved)
+    assert np.allclose(a, b, rtol=0, atol=1e-13)
+
+
+def test_rows_without_keys_carry_the_empty_state_through():
+    rng = np.random.default_rng(14)
+    q, k, v = _rand_qkv(rng, 1, 1, 1, 5, 3, 4)
+    st = oa.attn_state(q, k, v, True, 1.0)                 # Lq > Lk: rows 0, 1 see nothing
+    assert np.all(st[0, 0, :2, :4] == 0) and np.all(np.isneginf(st[0, 0, :2, 4]))
+    nxt = oa.attn_state(q, k, v, True, 1.0, st, shift=1)   # a second chunk they do see
+    alone = oa.attn_state(q, k, v, True, 1.0, None, shift=1)
+    assert np.allclose(nxt[0, 0, :2], alone[0, 0, :2], rtol=0, atol=1e-13)
+
+
+def test_state_matches_the_scalar_recurrence():
+    rng = np.random.default_rng(15)
+    q, k, v = _rand_qkv(rng, 1, 1, 1, 1, 6, 3, 2.0)
+    st = oa.attn_state(q, k, v, False, 0.7)[0, 0, 0]
+    s = (k[0, 0].double() @ q[0, 0, 0].double()).numpy() * float(np.float32(0.7))
+    o, lam = rec.state_of_run(s, v[0, 0].double().numpy())
+    assert np.allclose(st[:3], o, atol=1e-13) and abs((st[3] - st[4]) - lam) < 1e-12
+    _, lnw = rec.weights_sigmoid(s)
+    assert abs(st[3] - s[-1]) < 1e-13 and abs(st[4] - lnw[-1]) < 1e-12
