@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
     ap.add_argument("--no-ablation", action="store_true")
+    ap.add_argument("--no-state", action="store_true",
+                    help="skip the two-chunk run through flashd_attn_fwd_state")
     ap.add_argument("--no-skip-stats", action="store_true",
                     help="skip the static skip-range statistics (Sec. III-C) of two workloads")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -158,6 +160,26 @@ def main() -> int:
         ws = synthetic.CONFIGS[4]
         qs_, ks_, _, _ = synthetic.make_qkv(ws)
         out["skip_stats"] = [rates(w, sets[0][0], sets[0][1]), rates(ws, qs_.cuda(), ks_.cuda())]
+
+    if not args.no_state:
+        # the same workload fed as two chunks of keys with the Alg. 3 state handed on
+        # (flashd_attn_fwd_state): chunked prefill through the state primitive
+        qg, kg, vg, og = sets[0]
+        half = w.Lk // 2
+        kc = [kg[:, :, :half].contiguous(), kg[:, :, half:].contiguous()]
+        vc = [vg[:, :, :half].contiguous(), vg[:, :, half:].contiguous()]
+        st = torch.empty(w.B, w.Hq, w.Lq, w.d + 2, dtype=torch.float32, device="cuda")
+
+        def step_state(_i):
+            flashd.attn_fwd_state(qg, kc[0], vc[0], w.causal, w.scale, state_out=st,
+                                  causal_shift=w.Lk - w.Lq)
+            flashd.attn_fwd_state(qg, kc[1], vc[1], w.causal, w.scale, o=og, state_in=st,
+                                  causal_shift=w.Lk - w.Lq - half)
+        _, ev_st = time_calls(step_state, max(5, args.steps // 5), 2, 1)
+        ms_st = ev_st / max(5, args.steps // 5)
+        out["state_two_chunks"] = {"ms_per_step": round(ms_st, 4),
+                                   "TFLOP/s": round(flops / (ms_st * 1e-3) / 1e12, 2)}
+        del kc, vc, st
 
     del sets
     torch.cuda.empty_cache()

@@ -141,8 +141,8 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
     const int sp = splits == 0 ? auto_splits(s, var) : splits;
     // The state entry point always goes through partial states; a single partial may be
-    // written straight into the caller's state buffer.
-    const bool direct = sa.on && sp == 1 && sa.out != nullptr;
+    // written straight into the caller's state buffer (unless that is also the input state).
+    const bool direct = sa.on && sp == 1 && sa.out != nullptr && sa.out != sa.in;
     const size_t need = sa.on ? (direct ? 0 : partial_bytes(s, sp)) : ws_bytes(s, sp);
     if (!use_cache && need > 0 && (workspace == nullptr || workspace_bytes < need))
         return FLASHD_E_WORKSPACE;

@@ -148,3 +148,21 @@ def test_skip_stats_argument_errors():
     assert stats(q=P + 8) == E_ALIGN
     assert stats(counts=P + 4) == E_ALIGN
     assert stats(counts=P + 8) != E_ALIGN          # 8-byte alignment is enough for the counters
+
+
+def fwd_state(q=P, k=P, v=P, o=P, sin=None, sout=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=512, d=64,
+              dtype=flashd.BF16):
+    return flashd.raw().flashd_attn_fwd_state(q, k, v, o, sin, sout, B, Hq, Hkv, Lq, Lk, d, 1, 0,
+                                              1.0, dtype, None)
+
+
+def test_state_entry_point_argument_errors():
+    for name in ("q", "k", "v"):
+        assert fwd_state(**{name: None}) == E_NULL
+    assert fwd_state(o=None, sout=None) == E_NULL            # nothing to write
+    assert fwd_state(o=None) != E_NULL and fwd_state(sout=None) != E_NULL
+    assert fwd_state(Lq=0) == E_SHAPE
+    assert fwd_state(d=96) == E_HEADDIM
+    assert fwd_state(Hq=3) == E_GQA
+    assert fwd_state(sin=P + 4) == E_ALIGN
+    assert fwd_state(sout=P + 8) == E_ALIGN
