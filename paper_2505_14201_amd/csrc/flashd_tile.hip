@@ -28,10 +28,8 @@
 // are copied global->LDS directly (no registers), with an XOR chunk swizzle instead of
 // row padding.
 //
-// Launch order: workgroup ids run over (row tile, split, b*Hq + h) with the row tile
-// slowest and, under a causal mask, longest first, so the short tiles fill the tail.
-// Workgroups of one head are B*Hq*splits apart, a multiple of 8 for the usual shapes, and
-// therefore land on the same XCD and share its L2 for K and V.
+// Work hand-out: see TileSched below (virtual workgroups, causal row tiles paired long
+// with short, workgroups of a head kept on one XCD so that its K and V stay in that L2).
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
@@ -406,7 +404,6 @@ template <typename T, int D, bool ONLINE>
 __global__ __launch_bounds__(kNW * 64, 2)
 void tile_kernel(Problem p, TileSched sc) {
     using C = TileCfg<D>;
-    constexpr int kBM = 32 * kNW;     // query rows per workgroup
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
     constexpr int kTile = kBC * D;    // elements of one K or V tile
