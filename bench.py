@@ -54,6 +54,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
     ap.add_argument("--no-ablation", action="store_true")
+    ap.add_argument("--no-kv8", action="store_true", help="skip the fp8 K/V decode measurement")
     ap.add_argument("--no-state", action="store_true",
                     help="skip the two-chunk run through flashd_attn_fwd_state")
     ap.add_argument("--no-skip-stats", action="store_true",
@@ -202,6 +203,24 @@ def main() -> int:
                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
                                       "traffic": TRAFFIC_DECODE_BYTES}}
+        if not args.no_kv8:
+            # the same decode workload with K and V stored as fp8 (flashd_attn_fwd_kv8)
+            ks_, vs_ = 2.0 ** -5, 2.0 ** -5
+            k8 = (kd.float() / ks_).to(torch.float8_e4m3fn).cuda()
+            v8 = (vd.float() / vs_).to(torch.float8_e4m3fn).cuda()
+
+            def step_kv8(_):
+                flashd.attn_fwd_kv8(qg, k8, v8, og, wd.causal, wd.scale, ks_, vs_)
+            _, ev8 = time_calls(step_kv8, dsteps, 5, 1)
+            ms8 = ev8 / dsteps
+            bytes8 = k8.numel() + v8.numel() + 2 * qg.numel() * qg.element_size()
+            gbs8 = bytes8 / (ms8 * 1e-3) / 1e9
+            out["decode_fp8_kv"] = {"ms_per_step": round(ms8, 4), "bytes_per_step": bytes8,
+                                    "speedup_vs_bf16_kv": round(dms / ms8, 3),
+                                    "roofline": {"bound": "hbm", "achieved": round(gbs8, 1),
+                                                 "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                 "frac": round(gbs8 / PEAK_HBM_GBS, 4),
+                                                 "traffic": None}}
     print(json.dumps(out))
     return 0
 

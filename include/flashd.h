@@ -127,6 +127,22 @@ int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
                           int causal, int causal_shift, float scale, int dtype, void* stream);
 
 /*
+ * Attention forward with K and V stored as fp8 (the paper's second storage format, Sec. IV:
+ * FP8-E4M3; here the OCP encoding, no infinities, 0x7f / 0xff = NaN), one byte per element,
+ * same [B][Hkv][Lk][d] layout.  The real key and value are kscale * k8 and vscale * v8; q and
+ * o are in the storage type `dtype` (FLASHD_F16 or FLASHD_BF16).  K and V cross HBM as fp8
+ * and are widened exactly to `dtype` inside the kernel; everything else is the arithmetic
+ * of flashd_attn_fwd (kscale joins the score scale, vscale the output).
+ * This version serves the split-K decode shape only: (Hq / Hkv) * Lq <= 32, else
+ * FLASHD_E_VARIANT (also for FLASHD_F32).  Other conventions and errors as for
+ * flashd_attn_fwd, including the grow-only scratch cache.
+ */
+int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o,
+                        int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                        int causal, float scale, float kscale, float vscale, int dtype,
+                        void* stream);
+
+/*
  * Static skip statistics (Sec. III-C; the quantity reported in Table I).  Over every query
  * row and every step i >= 2 of Alg. 3 on that row's visible keys (same layout, head mapping
  * and causal rule as above; v is not needed), counts

@@ -126,9 +126,15 @@ struct StateArgs {
     float* out = nullptr;
 };
 
+struct Kv8Args {
+    bool on = false;                 // k and v are fp8 (e4m3) with one scale each
+    float kscale = 1.0f, vscale = 1.0f;
+};
+
 int run(const void* q, const void* k, const void* v, void* o, const Shape& s, int causal,
         float scale, void* stream, int variant, int splits, void* workspace,
-        size_t workspace_bytes, bool use_cache, const StateArgs& sa = StateArgs()) {
+        size_t workspace_bytes, bool use_cache, const StateArgs& sa = StateArgs(),
+        const Kv8Args& k8 = Kv8Args()) {
     if (!q || !k || !v) return FLASHD_E_NULL;
     if (!o && !(sa.on && sa.out)) return FLASHD_E_NULL;
     int rc = validate_shape(s);
@@ -138,6 +144,9 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     if (bits & 15u) return FLASHD_E_ALIGN;
     const int var = resolve_variant(s, variant);
     if (var < 0) return FLASHD_E_VARIANT;
+    // fp8 K/V: only the split-K decode kernel reads that storage
+    if (k8.on && (s.dtype == FLASHD_F32 || !flashd::decode_applies(s.Hq, s.Hkv, s.Lq)))
+        return FLASHD_E_VARIANT;
     if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
     const int sp = splits == 0 ? auto_splits(s, var) : splits;
     // The state entry point always goes through partial states; a single partial may be
@@ -167,6 +176,9 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.partial = (sp > 1 || sa.on) ? 1 : 0;
     p.state_in = sa.in;
     p.state_out = sa.out;
+    p.kv8 = k8.on ? 1 : 0;
+    p.kscale = k8.kscale;
+    p.vscale = k8.vscale;
     if (direct) p.ws = sa.out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -209,6 +221,18 @@ int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
     return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true, sa);
 }
 
+int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o, int B, int Hq,
+                        int Hkv, int Lq, int Lk, int d, int causal, float scale, float kscale,
+                        float vscale, int dtype, void* stream) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    Kv8Args a;
+    a.on = true;
+    a.kscale = kscale;
+    a.vscale = vscale;
+    return run(q, k8, v8, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true,
+               StateArgs(), a);
+}
+
 int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
                       int causal, float scale, int dtype, float lo, float hi,
                       unsigned long long* counts, void* stream) {
@@ -231,6 +255,8 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.partial = 0;
     p.state_in = nullptr;
     p.state_out = nullptr;
+    p.kv8 = 0;
+    p.kscale = p.vscale = 1.0f;
     const hipError_t e =
         flashd::launch_skip_stats(p, lo, hi, counts, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;

@@ -22,6 +22,8 @@ struct Problem {
     float scale;
     int shift;          // causal: key j is visible to query i iff j <= i + shift
     int partial;        // 1: the main kernel writes partial states to ws (always with splits > 1)
+    int kv8;            // 1: k and v hold fp8 (e4m3) elements, scaled by kscale / vscale
+    float kscale, vscale;
     const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32
     float* state_out;        // optional state after this call's keys, same layout
 };

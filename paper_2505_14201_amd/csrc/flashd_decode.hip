@@ -15,6 +15,12 @@
 // loads (a block is one contiguous 32 * d * 2 byte range) into registers while the
 // current block is being multiplied; V stays row-major in LDS and is read through the
 // transposing LDS load.
+//
+// KV8: K and V are stored as fp8 (e4m3, the paper's second format, Sec. IV), one byte per
+// element, with one scale each.  They cross HBM in that form (half the bytes per key) and
+// are widened exactly to the storage type of Q on the way from registers into the LDS
+// stage, so everything after the stage is the same arithmetic; kscale joins the score scale
+// and vscale the output.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
@@ -40,7 +46,31 @@ __device__ __forceinline__ void fetch_block(const uint16_t* kg, const uint16_t* 
     }
 }
 
-template <typename T, int D, bool ONLINE>
+// The same for fp8 storage: 16 elements (16 bytes) per chunk.
+template <int D, int CH8>
+__device__ __forceinline__ void fetch_block8(const uint8_t* kg, const uint8_t* vg, int j0, int Lk,
+                                             int lane, u32x4 (&kreg)[CH8], u32x4 (&vreg)[CH8]) {
+#pragma unroll
+    for (int n = 0; n < CH8; ++n) {
+        const int c = n * kWave + lane;            // 16-element chunk index inside the block
+        const int key = c / (D / 16);
+        const int part = c % (D / 16);
+        const size_t off = (size_t)min(j0 + key, Lk - 1) * D + 16 * part;
+        kreg[n] = *reinterpret_cast<const u32x4*>(kg + off);
+        vreg[n] = *reinterpret_cast<const u32x4*>(vg + off);
+    }
+}
+
+// 16 fp8 values -> 16 values of the storage type T (two 16-byte LDS chunks)
+template <typename T>
+__device__ __forceinline__ void widen16(u32x4 raw, u32x4& lo, u32x4& hi) {
+    lo = u32x4{Mma<T>::from_fp8_lo(raw[0]), Mma<T>::from_fp8_hi(raw[0]),
+               Mma<T>::from_fp8_lo(raw[1]), Mma<T>::from_fp8_hi(raw[1])};
+    hi = u32x4{Mma<T>::from_fp8_lo(raw[2]), Mma<T>::from_fp8_hi(raw[2]),
+               Mma<T>::from_fp8_lo(raw[3]), Mma<T>::from_fp8_hi(raw[3])};
+}
+
+template <typename T, int D, bool ONLINE, bool KV8>
 __global__ __launch_bounds__(kDecThreads, 2)
 void decode_kernel(Problem p) {
     constexpr int KROW = D + 8;                 // padded LDS rows (elements)
@@ -80,10 +110,11 @@ void decode_kernel(Problem p) {
     const int nvis_max = visible_count(p, p.Lq - 1);
     const int nvis = row_ok ? visible_count(p, qi) : nvis_max;
 
-    const uint16_t* kg = static_cast<const uint16_t*>(p.k) +
-                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
-    const uint16_t* vg = static_cast<const uint16_t*>(p.v) +
-                         ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
+    const size_t kv_off = ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;       // elements
+    const uint16_t* kg = static_cast<const uint16_t*>(p.k) + kv_off;
+    const uint16_t* vg = static_cast<const uint16_t*>(p.v) + kv_off;
+    const uint8_t* kg8 = static_cast<const uint8_t*>(p.k) + kv_off;
+    const uint8_t* vg8 = static_cast<const uint8_t*>(p.v) + kv_off;
 
     // 32-key blocks of this split; wavefront w takes blk_begin + w, + 4, ...
     const int nblk = (nvis_max + kDecBlock - 1) / kDecBlock;
@@ -95,7 +126,7 @@ void decode_kernel(Problem p) {
     uint16_t* ks = lds + wave * STAGE;
     uint16_t* vs = ks + kDecBlock * KROW;
 
-    const float c_log2 = p.scale * kLog2e;
+    const float c_log2 = (KV8 ? p.scale * p.kscale : p.scale) * kLog2e;
     const float ninf = -__builtin_inff();
     f32x16 U[NDB];
 #pragma unroll
@@ -105,23 +136,44 @@ void decode_kernel(Problem p) {
     float lam = ninf;
     float beta = ONLINE ? 0.0f : 1.0f;
 
-    u32x4 kreg[CH], vreg[CH];      // native vectors: HIP's uint4 struct would live in scratch
+    constexpr int CHR = KV8 ? CH / 2 : CH;     // 16-byte loads per lane, block and tensor
+    // One block per wavefront is in flight while the previous one is multiplied.  (Two in
+    // flight for the half-sized fp8 blocks were tried: the second register set spilled and
+    // the kernel got slower.)
+    u32x4 kreg[CHR], vreg[CHR];    // native vectors: HIP's uint4 struct would live in scratch
+    auto fetch = [&](int blk_) __attribute__((always_inline)) {
+        if constexpr (KV8)
+            fetch_block8<D, CHR>(kg8, vg8, blk_ * kDecBlock, p.Lk, lane, kreg, vreg);
+        else
+            fetch_block<D, CHR>(kg, vg, blk_ * kDecBlock, p.Lk, lane, kreg, vreg);
+    };
     int blk = blk_begin + wave;
-    if (blk < blk_end) fetch_block<D, CH>(kg, vg, blk * kDecBlock, p.Lk, lane, kreg, vreg);
+    if (blk < blk_end) fetch(blk);
     while (blk < blk_end) {
         const int j0 = blk * kDecBlock;
         // registers -> this wavefront's LDS stage
 #pragma unroll
-        for (int n = 0; n < CH; ++n) {
+        for (int n = 0; n < CHR; ++n) {
             const int c = n * kWave + lane;
-            const int key = c / (D / 8);
-            const int part = c % (D / 8);
-            *reinterpret_cast<u32x4*>(&ks[key * KROW + 8 * part]) = kreg[n];
-            *reinterpret_cast<u32x4*>(&vs[key * VROW + 8 * part]) = vreg[n];
+            if constexpr (KV8) {
+                const int key = c / (D / 16);
+                const int part = c % (D / 16);
+                u32x4 lo, hi;
+                widen16<T>(kreg[n], lo, hi);
+                *reinterpret_cast<u32x4*>(&ks[key * KROW + 16 * part]) = lo;
+                *reinterpret_cast<u32x4*>(&ks[key * KROW + 16 * part + 8]) = hi;
+                widen16<T>(vreg[n], lo, hi);
+                *reinterpret_cast<u32x4*>(&vs[key * VROW + 16 * part]) = lo;
+                *reinterpret_cast<u32x4*>(&vs[key * VROW + 16 * part + 8]) = hi;
+            } else {
+                const int key = c / (D / 8);
+                const int part = c % (D / 8);
+                *reinterpret_cast<u32x4*>(&ks[key * KROW + 8 * part]) = kreg[n];
+                *reinterpret_cast<u32x4*>(&vs[key * VROW + 8 * part]) = vreg[n];
+            }
         }
         const int nxt = blk + kDecWaves;
-        if (nxt < blk_end)                             // in flight during the math below
-            fetch_block<D, CH>(kg, vg, nxt * kDecBlock, p.Lk, lane, kreg, vreg);
+        if (nxt < blk_end) fetch(nxt);                 // in flight during the math below
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -172,6 +224,7 @@ void decode_kernel(Problem p) {
     // ---- fold the four wavefront states (sigmoid rule on runs of keys) --------------
     float fin, lam_out;
     row_finish<ONLINE>(lam, beta, fin, lam_out);
+    if (KV8) fin *= p.vscale;
     __syncthreads();                                   // stages are dead, reuse the LDS
     float* st = reinterpret_cast<float*>(lds);         // [wave][row][D + 1]
     constexpr int SROW = D + 1;
@@ -220,10 +273,14 @@ void decode_kernel(Problem p) {
 template <typename T, int D>
 static hipError_t launch_decode_t(const Problem& p, bool online, hipStream_t st) {
     dim3 grid((unsigned)p.splits, (unsigned)p.Hkv, (unsigned)p.B);
-    if (online)
-        hipLaunchKernelGGL((decode_kernel<T, D, true>), grid, dim3(kDecThreads), 0, st, p);
-    else
-        hipLaunchKernelGGL((decode_kernel<T, D, false>), grid, dim3(kDecThreads), 0, st, p);
+    if (p.kv8) {
+        if (online) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((decode_kernel<T, D, false, true>), grid, dim3(kDecThreads), 0, st, p);
+    } else if (online) {
+        hipLaunchKernelGGL((decode_kernel<T, D, true, false>), grid, dim3(kDecThreads), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((decode_kernel<T, D, false, false>), grid, dim3(kDecThreads), 0, st, p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !p.partial) return e;
     return launch_merge_splits(p, st);

@@ -41,6 +41,13 @@ template <> struct Mma<BF16> {
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, bf16x4));
     }
+    // two fp8 (e4m3) values of a dword -> two storage-type values, exact (scale 1)
+    static __device__ __forceinline__ uint32_t from_fp8_lo(uint32_t w) {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+    }
+    static __device__ __forceinline__ uint32_t from_fp8_hi(uint32_t w) {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
+    }
 };
 template <> struct Mma<F16> {
     static constexpr float kTheta = 14.0f;      // 2^14 is representable in fp16
@@ -53,6 +60,12 @@ template <> struct Mma<F16> {
     }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, f16x4));
+    }
+    static __device__ __forceinline__ uint32_t from_fp8_lo(uint32_t w) {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false));
+    }
+    static __device__ __forceinline__ uint32_t from_fp8_hi(uint32_t w) {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true));
     }
 };
 

@@ -22,7 +22,8 @@ MAX_SPLITS = 64
 _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
-           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state")
+           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
+           "flashd_attn_fwd_kv8")
 
 
 class FlashdError(RuntimeError):
@@ -49,6 +50,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_auto_splits.argtypes = [i] * 8
     lib.flashd_attn_fwd_state.restype = i
     lib.flashd_attn_fwd_state.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, f, i, p]
+    lib.flashd_attn_fwd_kv8.restype = i
+    lib.flashd_attn_fwd_kv8.argtypes = [p, p, p, p, i, i, i, i, i, i, i, f, f, f, i, p]
     lib.flashd_skip_stats.restype = i
     lib.flashd_skip_stats.argtypes = [p, p, i, i, i, i, i, i, i, f, i, f, f, p, p]
     lib.flashd_status_string.restype = ctypes.c_char_p
@@ -192,5 +195,29 @@ def attn_fwd_state(q, k, v, causal: bool, scale: float, o=None, state_in=None, s
                                         ptr(state_in), ptr(state_out), B, Hq, Hkv, Lq, Lk, d,
                                         int(bool(causal)), shift, float(scale), _DTYPE[q.dtype],
                                         _stream_ptr(stream))
+    if rc != 0:
+        raise FlashdError(rc)
+
+
+def attn_fwd_kv8(q, k8, v8, o, causal: bool, scale: float, kscale: float, vscale: float,
+                 stream=None) -> None:
+    """flashd_attn_fwd_kv8: K and V as torch.float8_e4m3fn tensors [B, Hkv, Lk, d] (the real
+    values are kscale * k8 and vscale * v8); q and o float16 or bfloat16."""
+    for name, t in (("q", q), ("k8", k8), ("v8", v8), ("o", o)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if q.dtype not in (torch.float16, torch.bfloat16) or o.dtype != q.dtype or o.shape != q.shape:
+        raise ValueError("q and o must be float16 or bfloat16 tensors of one shape")
+    if k8.dtype != torch.float8_e4m3fn or v8.dtype != k8.dtype or v8.shape != k8.shape:
+        raise ValueError("k8 and v8 must be float8_e4m3fn tensors of one shape")
+    B, Hq, Lq, d = q.shape
+    Bk, Hkv, Lk, dk = k8.shape
+    if Bk != B or dk != d:
+        raise ValueError("batch or head dimension mismatch between q and k8")
+    with torch.cuda.device(q.device):
+        rc = _lib.flashd_attn_fwd_kv8(q.data_ptr(), k8.data_ptr(), v8.data_ptr(), o.data_ptr(),
+                                      B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale),
+                                      float(kscale), float(vscale), _DTYPE[q.dtype],
+                                      _stream_ptr(stream))
     if rc != 0:
         raise FlashdError(rc)

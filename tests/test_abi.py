@@ -36,7 +36,7 @@ def fwd_ex(variant=0, splits=0, ws=None, ws_bytes=0, **kw):
 def test_header_symbols_are_exported():
     text = open(os.path.join(ROOT, "include", "flashd.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(flashd_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(flashd_[a-z0-9_]+)\s*\(", text))
     assert declared == set(flashd.EXPORTS)
     lib = ctypes.CDLL(flashd.LIB_PATH)
     for name in declared:
@@ -166,3 +166,20 @@ def test_state_entry_point_argument_errors():
     assert fwd_state(Hq=3) == E_GQA
     assert fwd_state(sin=P + 4) == E_ALIGN
     assert fwd_state(sout=P + 8) == E_ALIGN
+
+
+def fwd_kv8(q=P, k=P, v=P, o=P, B=1, Hq=8, Hkv=2, Lq=1, Lk=512, d=128, dtype=flashd.BF16):
+    return flashd.raw().flashd_attn_fwd_kv8(q, k, v, o, B, Hq, Hkv, Lq, Lk, d, 0, 1.0, 1.0, 1.0,
+                                            dtype, None)
+
+
+def test_fp8_entry_point_argument_errors():
+    for name in ("q", "k", "v", "o"):
+        assert fwd_kv8(**{name: None}) == E_NULL
+    assert fwd_kv8(Lk=0) == E_SHAPE
+    assert fwd_kv8(d=72) == E_HEADDIM
+    assert fwd_kv8(Hq=7) == E_GQA
+    assert fwd_kv8(k=P + 8) == E_ALIGN
+    assert fwd_kv8(dtype=flashd.F32) == E_VARIANT            # q and o must be f16 or bf16
+    assert fwd_kv8(Hq=8, Hkv=2, Lq=9) == E_VARIANT           # 36 query rows per kv head
+    assert fwd_kv8(Hq=8, Hkv=2, Lq=8) not in (E_VARIANT, E_NULL, E_SHAPE, E_ALIGN)
