@@ -133,13 +133,14 @@ void decode_kernel(Problem p) {
     for (int i = 0; i < NDB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) U[i][r] = 0.0f;
-    float lam = ninf;
-    float beta = ONLINE ? 0.0f : 1.0f;
+    LazyRow st = {0.0f, 1.0f, 0.0f};      // FLASH-D state of the lane's row
+    float lam = ninf, beta = 0.0f;         // Alg. 2 state: running max, running sum
+    bool first = true;
 
     constexpr int CHR = KV8 ? CH / 2 : CH;     // 16-byte loads per lane, block and tensor
-    // One block per wavefront is in flight while the previous one is multiplied.  (Two in
-    // flight for the half-sized fp8 blocks were tried: the second register set spilled and
-    // the kernel got slower.)
+    // One block per wavefront is in flight while the previous one is multiplied.  (Two
+    // register sets for the half-sized fp8 blocks were tried and were slower: the kernel is
+    // bound by instruction issue there, not by memory latency.)
     u32x4 kreg[CHR], vreg[CHR];    // native vectors: HIP's uint4 struct would live in scratch
     auto fetch = [&](int blk_) __attribute__((always_inline)) {
         if constexpr (KV8)
@@ -172,8 +173,7 @@ void decode_kernel(Problem p) {
                 *reinterpret_cast<u32x4*>(&vs[key * VROW + 8 * part]) = vreg[n];
             }
         }
-        const int nxt = blk + kDecWaves;
-        if (nxt < blk_end) fetch(nxt);                 // in flight during the math below
+        if (blk + kDecWaves < blk_end) fetch(blk + kDecWaves);     // in flight during the math
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -187,49 +187,61 @@ void decode_kernel(Problem p) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(&ks[col * KROW + 16 * kk + 8 * hh]);
             acc[0] = Mma<T>::mfma(a, qf[kk], acc[0]);
         }
-        const bool need_mask = j0 + kDecBlock > nvis_min;
+        // Coefficients of the block and the per-row state update (flashd_mma.h): the blend
+        // factor is carried as a scalar per row, U is only scaled on the rare overflow path.
+        // general: keys may be masked, or rows may still be empty (the wavefront's first block).
+        const bool general = first || j0 + kDecBlock > nvis_min;
+        first = false;
+        const int jb = j0 + 4 * hh;
+        u32x4 bfrag[2];
+        if (!ONLINE) {
+            bool risky;
+            if (general) risky = lazy_spec_pack<T, 1, true, true>(acc, bfrag, st, c_log2, jb, nvis, lane);
+            else risky = lazy_spec_pack<T, 1, false, false>(acc, bfrag, st, c_log2, jb, nvis, lane);
+            if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+                const float f = lazy_redo_pack<T, 1>(acc, bfrag, st, risky, c_log2, general, jb, nvis);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float s = acc[0][r] * c_log2;
-            if (need_mask) {
-                const int j = j0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                if (j >= nvis) s = ninf;
+                for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) U[i][r] *= f;
             }
-            acc[0][r] = s;
+        } else {
+            float f;
+            if (general) f = online_pack<T, 1, true>(acc, bfrag, lam, beta, c_log2, jb, nvis);
+            else f = online_pack<T, 1, false>(acc, bfrag, lam, beta, c_log2, jb, nvis);
+#pragma unroll
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) U[i][r] *= f;
         }
-        const float f = row_step<T, 1, ONLINE>(acc, lam, beta);
-
-#pragma unroll
-        for (int i = 0; i < NDB; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) U[i][r] *= f;
 #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2) {
-            f32x8 pv;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pv[e] = acc[0][8 * g2 + e];
-            const u32x4 bfrag = Mma<T>::pack8(pv);
 #pragma unroll
             for (int i = 0; i < NDB; ++i) {
                 const u32x4 a = lds_read_v_operand(&vs[(16 * g2) * VROW + 32 * i], VROW, lane);
-                U[i] = Mma<T>::mfma(a, bfrag, U[i]);
+                U[i] = Mma<T>::mfma(a, bfrag[g2], U[i]);
             }
         }
         // the next stage write must not overtake these LDS reads
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        blk = nxt;
+        blk += kDecWaves;
     }
 
     // ---- fold the four wavefront states (sigmoid rule on runs of keys) --------------
     float fin, lam_out;
-    row_finish<ONLINE>(lam, beta, fin, lam_out);
+    if (!ONLINE) {
+        fin = st.beta;                     // the state is the output: o = beta U
+        lam_out = st.one == 0.0f ? ninf : st.R - log2_fast(st.beta);
+    } else {
+        row_finish<true>(lam, beta, fin, lam_out);
+    }
     if (KV8) fin *= p.vscale;
     __syncthreads();                                   // stages are dead, reuse the LDS
-    float* st = reinterpret_cast<float*>(lds);         // [wave][row][D + 1]
+    float* fold = reinterpret_cast<float*>(lds);       // [wave][row][D + 1]
     constexpr int SROW = D + 1;
     if (row_ok) {
-        float* dst = st + ((size_t)wave * 32 + col) * SROW;
+        float* dst = fold + ((size_t)wave * 32 + col) * SROW;
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -245,7 +257,7 @@ void decode_kernel(Problem p) {
         float lm = ninf;
 #pragma unroll
         for (int w = 0; w < kDecWaves; ++w) {
-            const float* src = st + ((size_t)w * 32 + row) * SROW;
+            const float* src = fold + ((size_t)w * 32 + row) * SROW;
             const float lb = src[D];
             if (lb == ninf) continue;                  // empty run: identity
             if (lm == ninf) { o = src[t]; lm = lb; continue; }

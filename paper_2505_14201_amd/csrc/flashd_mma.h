@@ -29,8 +29,6 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 template <typename T> struct Mma;
 template <> struct Mma<BF16> {
-    // log2 units: 2^{s - Lam} <= 2^60, and 64 of them times |v|, stay far below fp32 overflow
-    static constexpr float kTheta = 60.0f;
     static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -50,7 +48,6 @@ template <> struct Mma<BF16> {
     }
 };
 template <> struct Mma<F16> {
-    static constexpr float kTheta = 14.0f;      // 2^14 is representable in fp16
     static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
@@ -103,102 +100,11 @@ __device__ __forceinline__ u32x4 lds_read_v_operand(const uint16_t* base, int ro
     return u32x4{l2[0], l2[1], h2[0], h2[1]};
 }
 
-// One tile of keys for one query row.  On entry acc[][] holds the row's scores in log2
-// units (masked keys: -inf) in the accumulator layout, the row being shared by lanes l
-// and l ^ 32.  On exit acc[][] holds the coefficients p_j to be rounded and multiplied
-// with V; the return value is the factor the row's accumulator U must be scaled by BEFORE
-// p V is added.  State:
-//   FLASH-D (ONLINE = false): lam = Lam = s_last - ln w_last in log2 units (-inf: no key
-//     yet); beta = factor still owed to U (true o = beta U).
-//   Alg. 2  (ONLINE = true):  lam = running max m, beta = running sum l (o = U / l).
-template <typename T, int NB, bool ONLINE>
-__device__ __forceinline__ float row_step(f32x16 (&acc)[NB], float& lam, float& beta) {
-    const float ninf = -__builtin_inff();
-    float f;
-    if (!ONLINE) {
-        // A row is "risky" when one of its scores exceeds Lam by more than kTheta, or Lam
-        // is still -inf (its first visible tile): then 2^{s - Lam} is not formed.  The
-        // choice is per row, so a row's result never depends on other rows' data.
-        bool risky = false;
-#pragma unroll
-        for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) risky |= !(acc[kb][r] - lam <= Mma<T>::kTheta);
-        risky |= (__shfl_xor((int)risky, 32, 64) != 0);
-        float ref = lam;          // exponent reference of this row for this tile
-        float lam_new = lam;
-        if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // key-by-key recurrence inside the lane: Lam_j = Lam_{j-1} + softplus(s_j -
-            // Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as
-            // Lam = s - ln w; the first visible key starts the run (w = 1).  The sigmoid
-            // saturates instead of overflowing, whatever the score jump (Sec. III-C).
-            float ll = ninf;
-#pragma unroll
-            for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float s = acc[kb][r];
-                    if (s != ninf) ll = lse2(ll, s);
-                }
-            ll = lse2(ll, __shfl_xor(ll, 32, 64));      // partner lane's run
-            lam_new = lse2(lam, ll);                      // the tile acts as one key
-            if (risky) ref = (lam_new == ninf) ? 0.0f : lam_new;
-        }
-        float psum = 0.0f;
-#pragma unroll
-        for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pj = exp2_fast(acc[kb][r] - ref);
-                psum += pj;
-                acc[kb][r] = pj;
-            }
-        psum += __shfl_xor(psum, 32, 64);
-        if (!risky) {
-            // tile rule: p_j = 2^{s_j - Lam}, tot = 1 + sum p_j, 1 - W = 1/tot
-            const float tot = 1.0f + psum;
-            f = beta;
-            beta = __builtin_amdgcn_rcpf(tot);
-            lam += log2_fast(tot);
-        } else {
-            // c_j = 2^{s_j - Lam_new} <= 1 is already final; the old state decays by
-            // 2^{Lam - Lam_new} = 1 - W
-            const float decay = (lam == ninf) ? 0.0f : exp2_fast(lam - lam_new);
-            f = beta * decay;
-            beta = 1.0f;
-            lam = lam_new;
-        }
-    } else {
-        // Alg. 2: m_i = max(m_{i-1}, s), l_i = l_{i-1} e^{m_{i-1}-m_i} + sum e^{s-m_i}
-        float mx = ninf;
-#pragma unroll
-        for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[kb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(lam, mx);
-        const float m_use = (m_new == ninf) ? 0.0f : m_new;
-        const float resc = exp2_fast(lam - m_use);
-        float psum = 0.0f;
-#pragma unroll
-        for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pj = exp2_fast(acc[kb][r] - m_use);
-                psum += pj;
-                acc[kb][r] = pj;
-            }
-        psum += __shfl_xor(psum, 32, 64);
-        beta = beta * resc + psum;
-        lam = m_new;
-        f = resc;
-    }
-    return f;
-}
-
 // ---------------------------------------------------------------------------
-// The same tile rule with the blend factor kept as a scalar ("lazy blend"), used by the
-// prefill kernel.  A row's state is (U, R, beta, one):
+// The tile rule of Alg. 3 with the blend factor kept as a scalar ("lazy blend"), used by the
+// prefill and the decode kernel.  After a run of keys the state of Alg. 3 is
+// (o, s_last, ln w_last) and only Lam = s_last - ln w_last enters later steps; a tile of keys
+// acts as one key.  A row's state here is (U, R, beta, one):
 //     true output o = beta U,   Lam = R - log2 beta,   one = 0 until the row has seen a key.
 // For a tile, with p_j = 2^{s_j - R} (R does not move on this path) and psum = sum_j p_j,
 //     tot = one + beta psum,   1 - W = 1/tot   (W = sigmoid(S_tile - Lam), the tile's weight),
