@@ -20,6 +20,9 @@ import torch
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
+# fp32 vector fma without packed instructions (this build compiles them out): 256 CUs x 4 SIMDs
+# x 16 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s, half the published 157.3 that counts packed issue
+PEAK_FP32_FMA = 78.6
 
 # HBM-side bytes per launch of the dominant kernel, from the profiler's FETCH_SIZE and
 # WRITE_SIZE counters scaled by a 1 GiB device copy (the summaries under profiles/ give the
@@ -156,8 +159,11 @@ def main() -> int:
             _, ms = time_calls(lambda _i: flashd.skip_stats(qg, kg, wl.causal, wl.scale,
                                                             counts=cnt), 3, 0, 1)
             steps, low, high = (int(x) for x in cnt.cpu())
+            tf = 2.0 * wl.d * steps / (ms / 3 * 1e-3) / 1e12      # one fp32 fma per element
             return {"workload": wl.name, "steps": steps, "low_frac": round(low / steps, 6),
-                    "high_frac": round(high / steps, 6), "kernel_ms": round(ms / 3, 3)}
+                    "high_frac": round(high / steps, 6), "kernel_ms": round(ms / 3, 3),
+                    "roofline": {"bound": "alu", "achieved": round(tf, 2), "peak": PEAK_FP32_FMA,
+                                 "unit": "TFLOP/s", "frac": round(tf / PEAK_FP32_FMA, 4)}}
         ws = synthetic.CONFIGS[4]
         qs_, ks_, _, _ = synthetic.make_qkv(ws)
         out["skip_stats"] = [rates(w, sets[0][0], sets[0][1]), rates(ws, qs_.cuda(), ks_.cuda())]

@@ -53,7 +53,12 @@ int auto_splits(const Shape& s, int variant) {
     } else {
         units = flashd::tile_workgroups(s.B, s.Hq, s.Hkv, s.Lq, s.d);
     }
-    const long target = 1024;
+    // Two workgroups are resident per compute unit (512 in all).  The decode kernel
+    // streams at the same rate with one full round of them as with several, so it is not
+    // split further once a round is full; the other kernels want two rounds for balance.
+    const bool decode = variant != FLASHD_VARIANT_PER_KEY &&
+                        flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
+    const long target = decode ? 512 : 1024;
     if (units < 1) units = 1;
     long sp = units >= target ? 1 : ceil_div(target, units);
     const long by_len = s.Lk / 256 > 0 ? s.Lk / 256 : 1;

@@ -7,11 +7,12 @@
 // the matrix-core kernels: acc = fma(q[t], k[t], acc) for t = 0 .. d-1 in this order in
 // fp32, s = acc * scale, diff = s_i - s_{i-1}, all single IEEE operations.
 //
-// Mapping: a wavefront owns a query row and walks the row's keys 64 at a time, a key per
-// lane; the lane's predecessor score comes from the neighbouring lane (from lane 63 of the
-// previous step for lane 0).  The query row is read as fp32 from LDS (every lane the same
-// address: a broadcast).  Workgroups walk the rows grid-stride and add their three counts
-// to the global counters once at the end.
+// Mapping: a wavefront owns kStatRows consecutive query rows of one head and walks their
+// keys 64 at a time, a key per lane, so that a key row is fetched once for all of them; the
+// lane's predecessor score comes from the neighbouring lane (from lane 63 of the previous
+// step for lane 0).  The query rows are read as fp32 from LDS (every lane the same address:
+// a broadcast).  Workgroups walk the row groups grid-stride and add their three counts to
+// the global counters once at the end.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 
@@ -21,56 +22,79 @@ __global__ void stats_clear_kernel(unsigned long long* counts) {
     if (threadIdx.x < 3) counts[threadIdx.x] = 0ull;
 }
 
+constexpr int kStatRows = 4;      // query rows per wavefront
+
 template <typename T, int D>
 __global__ __launch_bounds__(256)
 void skip_stats_kernel(Problem p, float lo, float hi, unsigned long long* counts) {
-    __shared__ float qs[4][D];
+    constexpr int R = kStatRows;
+    __shared__ __align__(16) float qs[4][R][D];
     __shared__ unsigned long long part[4][3];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const long rows = (long)p.B * p.Hq * p.Lq;
     const int g = p.Hq / p.Hkv;
+    const long groups_per_head = (p.Lq + R - 1) / R;
+    const long groups = (long)p.B * p.Hq * groups_per_head;
     unsigned long long steps = 0, low = 0, high = 0;     // this wavefront's counts (uniform)
 
-    for (long row = (long)blockIdx.x * 4 + wave; row < rows; row += (long)gridDim.x * 4) {
-        const int i = (int)(row % p.Lq);
-        const long bh = row / p.Lq;
+    for (long grp = (long)blockIdx.x * 4 + wave; grp < groups; grp += (long)gridDim.x * 4) {
+        const int i0 = (int)(grp % groups_per_head) * R;
+        const long bh = grp / groups_per_head;
         const int h = (int)(bh % p.Hq);
         const int b = (int)(bh / p.Hq);
-        const size_t qoff = (size_t)row * D;
+        const size_t qoff = (((size_t)b * p.Hq + h) * p.Lq + i0) * (size_t)D;
         const size_t koff = ((size_t)b * p.Hkv + h / g) * (size_t)p.Lk * D;
         // only this wavefront touches qs[wave]; the wave barriers order its own accesses
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        for (int t = lane; t < D; t += 64) qs[wave][t] = Store<T>::load(p.q, qoff + t);
+        int nvis[R];
+        int nmax = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = i0 + r;
+            const bool ok = i < p.Lq;
+            for (int t = lane; t < D; t += 64)
+                qs[wave][r][t] = ok ? Store<T>::load(p.q, qoff + (size_t)r * D + t) : 0.0f;
+            int n = p.Lk;
+            if (p.causal) n = min(max(i + p.shift + 1, 0), p.Lk);
+            nvis[r] = ok ? n : 0;
+            nmax = max(nmax, nvis[r]);
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        int nvis = p.Lk;
-        if (p.causal) nvis = min(max(i + p.shift + 1, 0), p.Lk);
-        float carry = 0.0f;                               // score of key j0 - 1
-        for (int j0 = 0; j0 < nvis; j0 += 64) {
+        float carry[R];                                   // score of key j0 - 1, per row
+#pragma unroll
+        for (int r = 0; r < R; ++r) carry[r] = 0.0f;
+        for (int j0 = 0; j0 < nmax; j0 += 64) {
             const int j = j0 + lane;
-            const bool valid = j < nvis;
-            const int jr = valid ? j : nvis - 1;          // clamped: loads stay in bounds
-            float acc = 0.0f;
+            const int jr = min(j, nmax - 1);              // clamped: loads stay in bounds
+            float acc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = 0.0f;
 #pragma unroll 2
             for (int t0 = 0; t0 < D; t0 += 8) {
                 float kf[8];
                 Store<T>::load8(p.k, koff + (size_t)jr * D + t0, kf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[wave][t0 + e], kf[e], acc);
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        acc[r] = __builtin_fmaf(qs[wave][r][t0 + e], kf[e], acc[r]);
             }
-            const float s = __fmul_rn(acc, p.scale);        // never fused with the subtraction
-            float prev = __shfl_up(s, 1, 64);
-            if (lane == 0) prev = carry;
-            const float diff = __fsub_rn(s, prev);
-            const bool step = valid && j > 0;
-            steps += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step));
-            low += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step && diff <= lo));
-            high += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step && diff >= hi));
-            carry = __shfl(s, 63, 64);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float s = __fmul_rn(acc[r], p.scale);    // never fused with the subtraction
+                float prev = __shfl_up(s, 1, 64);
+                if (lane == 0) prev = carry[r];
+                const float diff = __fsub_rn(s, prev);
+                const bool step = j < nvis[r] && j > 0;
+                steps += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step));
+                low += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step && diff <= lo));
+                high += __builtin_popcountll(__builtin_amdgcn_ballot_w64(step && diff >= hi));
+                carry[r] = __shfl(s, 63, 64);
+            }
         }
     }
     if (lane == 0) { part[wave][0] = steps; part[wave][1] = low; part[wave][2] = high; }
@@ -85,8 +109,8 @@ void skip_stats_kernel(Problem p, float lo, float hi, unsigned long long* counts
 template <typename T, int D>
 static hipError_t launch_stats_t(const Problem& p, float lo, float hi, unsigned long long* counts,
                                  hipStream_t st) {
-    const long rows = (long)p.B * p.Hq * p.Lq;
-    const long want = (rows + 3) / 4;
+    const long groups = (long)p.B * p.Hq * ((p.Lq + kStatRows - 1) / kStatRows);
+    const long want = (groups + 3) / 4;
     const unsigned grid = (unsigned)(want < 4096 ? want : 4096);
     hipLaunchKernelGGL(stats_clear_kernel, dim3(1), dim3(64), 0, st, counts);
     hipLaunchKernelGGL((skip_stats_kernel<T, D>), dim3(grid), dim3(256), 0, st, p, lo, hi, counts);
