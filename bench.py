@@ -27,8 +27,8 @@ PEAK_FP32_FMA = 78.6
 # HBM-side bytes per launch of the dominant kernel, from the profiler's FETCH_SIZE and
 # WRITE_SIZE counters scaled by a 1 GiB device copy (the summaries under profiles/ give the
 # commands and the raw readings); they cannot be read from inside this process.
-TRAFFIC_PREFILL_BYTES = 340.1e6
-TRAFFIC_DECODE_BYTES = 2150.8e6
+TRAFFIC_PREFILL_BYTES = 338.1e6
+TRAFFIC_DECODE_BYTES = 2148.6e6
 
 
 def time_calls(fn, steps, warmup, nsets):
