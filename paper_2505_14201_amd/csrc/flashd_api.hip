@@ -157,7 +157,11 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     // The state entry point always goes through partial states; a single partial may be
     // written straight into the caller's state buffer (unless that is also the input state).
     const bool direct = sa.on && sp == 1 && sa.out != nullptr && sa.out != sa.in;
-    const size_t need = sa.on ? (direct ? 0 : partial_bytes(s, sp)) : ws_bytes(s, sp);
+    // The tile kernel can start from the state itself and write both results: no partial
+    // states, no merge kernel.
+    const bool in_kernel = sa.on && sp == 1 && var == FLASHD_VARIANT_TILE &&
+                           !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
+    const size_t need = sa.on ? ((direct || in_kernel) ? 0 : partial_bytes(s, sp)) : ws_bytes(s, sp);
     if (!use_cache && need > 0 && (workspace == nullptr || workspace_bytes < need))
         return FLASHD_E_WORKSPACE;
 
@@ -179,12 +183,22 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.scale = scale;
     p.shift = sa.on ? sa.shift : s.Lk - s.Lq;
     p.partial = (sp > 1 || sa.on) ? 1 : 0;
+    p.store_o = p.partial ? 0 : 1;
+    p.merge = p.partial;
+    p.from_state = 0;
     p.state_in = sa.in;
     p.state_out = sa.out;
+    if (in_kernel) {
+        p.partial = sa.out != nullptr ? 1 : 0;     // the "partial" is the state handed out
+        p.store_o = o != nullptr ? 1 : 0;
+        p.merge = 0;
+        p.from_state = sa.in != nullptr ? 1 : 0;
+        p.ws = sa.out;
+    }
     p.kv8 = k8.on ? 1 : 0;
     p.kscale = k8.kscale;
     p.vscale = k8.vscale;
-    if (direct) p.ws = sa.out;
+    if (direct && !in_kernel) p.ws = sa.out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     const bool online = var == FLASHD_VARIANT_ONLINE_SOFTMAX;
@@ -258,6 +272,9 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.scale = scale;
     p.shift = Lk - Lq;
     p.partial = 0;
+    p.store_o = 0;
+    p.merge = 0;
+    p.from_state = 0;
     p.state_in = nullptr;
     p.state_out = nullptr;
     p.kv8 = 0;

@@ -22,6 +22,9 @@ struct Problem {
     float scale;
     int shift;          // causal: key j is visible to query i iff j <= i + shift
     int partial;        // 1: the main kernel writes partial states to ws (always with splits > 1)
+    int store_o;        // 1: the main kernel stores the output in the storage type
+    int merge;          // 1: merge_splits_kernel runs after the main kernel
+    int from_state;     // 1: the tile kernel starts every row from state_in (no merge needed)
     int kv8;            // 1: k and v hold fp8 (e4m3) elements, scaled by kscale / vscale
     float kscale, vscale;
     const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32

@@ -294,7 +294,7 @@ static hipError_t launch_decode_t(const Problem& p, bool online, hipStream_t st)
         hipLaunchKernelGGL((decode_kernel<T, D, false, false>), grid, dim3(kDecThreads), 0, st, p);
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !p.partial) return e;
+    if (e != hipSuccess || !p.merge) return e;
     return launch_merge_splits(p, st);
 }
 

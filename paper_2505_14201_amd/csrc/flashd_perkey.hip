@@ -214,7 +214,7 @@ static hipError_t launch_perkey_t(const Problem& p, hipStream_t st) {
     dim3 grid((unsigned)(row_blocks * p.splits), (unsigned)p.Hq, (unsigned)p.B);
     hipLaunchKernelGGL((perkey_kernel<T, D>), grid, dim3(kPerKeyWaves * kWave), 0, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !p.partial) return e;
+    if (e != hipSuccess || !p.merge) return e;
     return launch_merge_t<T, D>(p, st);
 }
 

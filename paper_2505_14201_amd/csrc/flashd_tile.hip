@@ -460,6 +460,25 @@ void tile_kernel(Problem p, TileSched sc) {
         g.st = {0.0f, 1.0f, 0.0f};
         g.lam = ninf;
         g.beta = 0.0f;
+        if (!ONLINE && p.from_state) {
+            // continue from the state of earlier keys: o = U with beta = 1, R = Lam
+            const int row = min(cur.wrow0 + col, p.Lq - 1);
+            const float* src = p.state_in +
+                               (((size_t)cur.b * p.Hq + cur.h) * (size_t)p.Lq + row) * (D + 2);
+            const float lam_in = src[D] - src[D + 1];            // s - ln w, natural log
+            if (cur.wrow0 + col < p.Lq && lam_in != ninf) {
+#pragma unroll
+                for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const float4 x =
+                            *reinterpret_cast<const float4*>(src + 32 * i + 8 * gq + 4 * hh);
+                        g.U[i][4 * gq + 0] = x.x; g.U[i][4 * gq + 1] = x.y;
+                        g.U[i][4 * gq + 2] = x.z; g.U[i][4 * gq + 3] = x.w;
+                    }
+                g.st = {lam_in * kLog2e, 1.0f, 1.0f};
+            }
+        }
 
         if (!have0 && cur.n > 0)
             tile_copy<D>(cur.kg, cur.vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
@@ -521,7 +540,7 @@ void tile_kernel(Problem p, TileSched sc) {
         asm volatile("" : "+v"(elane));
         const int col = elane & 31;
         const int hh = elane >> 5;
-        if (!p.partial) {
+        if (p.store_o) {
             // Stage the wavefront's 32 x D output block through LDS so that the global
             // stores are 16 bytes per lane and whole rows are contiguous.  Slot 1 is idle
             // after the last barrier and never the target of the copy of the next row
@@ -559,7 +578,8 @@ void tile_kernel(Problem p, TileSched sc) {
                 if (cur.wrow0 + r < p.Lq)
                     *reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
             }
-        } else if (cur.wrow0 + col < p.Lq) {
+        }
+        if (p.partial && cur.wrow0 + col < p.Lq) {
             // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
             float* dst = p.ws + ((((size_t)cur.sp * p.B + cur.b) * p.Hq + cur.h) * (size_t)p.Lq +
                                  cur.wrow0 + col) *
@@ -635,7 +655,7 @@ static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
     else
         hipLaunchKernelGGL((tile_kernel<T, D, false>), grid, dim3(kNW * 64), 0, st, p, sc);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !p.partial) return e;
+    if (e != hipSuccess || !p.merge) return e;
     return launch_merge_splits(p, st);
 }
 
