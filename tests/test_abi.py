@@ -183,3 +183,36 @@ def test_fp8_entry_point_argument_errors():
     assert fwd_kv8(dtype=flashd.F32) == E_VARIANT            # q and o must be f16 or bf16
     assert fwd_kv8(Hq=8, Hkv=2, Lq=9) == E_VARIANT           # 36 query rows per kv head
     assert fwd_kv8(Hq=8, Hkv=2, Lq=8) not in (E_VARIANT, E_NULL, E_SHAPE, E_ALIGN)
+
+
+def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
+    """A C99 program (no C++, no HIP headers) includes flashd.h, links against the shared
+    library and calls the entry points that need no GPU."""
+    import subprocess
+    src = tmp_path / "consumer.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "flashd.h"
+int main(void) {
+    unsigned long long counts[3];
+    if (flashd_version() < 100) return 1;
+    if (strcmp(flashd_status_string(FLASHD_OK), flashd_status_string(FLASHD_E_NULL)) == 0) return 2;
+    if (flashd_attn_fwd(NULL, NULL, NULL, NULL, 1, 1, 1, 1, 1, 64, 0, 1.0f, FLASHD_BF16, NULL)
+        != FLASHD_E_NULL) return 3;
+    if (flashd_skip_stats(NULL, NULL, 1, 1, 1, 1, 1, 64, 0, 1.0f, FLASHD_F32, -6.0f, 11.0f,
+                          counts, NULL) != FLASHD_E_NULL) return 4;
+    if (flashd_workspace_bytes(1, 4, 2, 8, 512, 64, FLASHD_BF16, FLASHD_VARIANT_PER_KEY, 4)
+        != (size_t)4 * 4 * 8 * 66 * 4) return 5;
+    printf("ok %d\n", flashd_version());
+    return 0;
+}
+''')
+    exe = tmp_path / "consumer"
+    libdir = os.path.dirname(flashd.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:" + os.path.basename(flashd.LIB_PATH),
+                    "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("ok ")
