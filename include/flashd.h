@@ -133,9 +133,10 @@ int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
  * o are in the storage type `dtype` (FLASHD_F16 or FLASHD_BF16).  K and V cross HBM as fp8
  * and are widened exactly to `dtype` inside the kernel; everything else is the arithmetic
  * of flashd_attn_fwd (kscale joins the score scale, vscale the output).
- * This version serves the split-K decode shape only: (Hq / Hkv) * Lq <= 32, else
- * FLASHD_E_VARIANT (also for FLASHD_F32).  Other conventions and errors as for
- * flashd_attn_fwd, including the grow-only scratch cache.
+ * For decode shapes ((Hq / Hkv) * Lq <= 32) the kernel reads the fp8 data itself; for other
+ * shapes K and V are first widened into scratch memory (2 * B * Hkv * Lk * d * 2 bytes from the
+ * grow-only cache) and the f16/bf16 kernel runs on that.  FLASHD_F32 gives FLASHD_E_VARIANT.
+ * Other conventions and errors as for flashd_attn_fwd.
  */
 int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o,
                         int B, int Hq, int Hkv, int Lq, int Lk, int d,

@@ -149,9 +149,10 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     if (bits & 15u) return FLASHD_E_ALIGN;
     const int var = resolve_variant(s, variant);
     if (var < 0) return FLASHD_E_VARIANT;
-    // fp8 K/V: only the split-K decode kernel reads that storage
-    if (k8.on && (s.dtype == FLASHD_F32 || !flashd::decode_applies(s.Hq, s.Hkv, s.Lq)))
-        return FLASHD_E_VARIANT;
+    // fp8 K/V: the split-K decode kernel reads that storage itself; for other shapes K and V
+    // are first widened (exactly) into scratch memory
+    if (k8.on && s.dtype == FLASHD_F32) return FLASHD_E_VARIANT;
+    const bool widen = k8.on && !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
     if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
     const int sp = splits == 0 ? auto_splits(s, var) : splits;
     // The state entry point always goes through partial states; a single partial may be
@@ -168,9 +169,25 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     rc = check_arch();
     if (rc != FLASHD_OK) return rc;
     void* ws = workspace;
+    const size_t need_al = (need + 255) & ~(size_t)255;
+    const size_t kv_bytes = widen ? (size_t)s.B * s.Hkv * s.Lk * s.d * 2 : 0;   // per tensor
     if (use_cache) {
-        rc = cached_workspace(stream, need, &ws);
+        rc = cached_workspace(stream, need_al + 2 * kv_bytes, &ws);
         if (rc != FLASHD_OK) return rc;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float score_scale = scale, out_scale = 1.0f;
+    bool kv8_kernel = k8.on;
+    if (widen) {
+        char* base = static_cast<char*>(ws) + need_al;
+        if (flashd::launch_widen_fp8(k, v, base, base + kv_bytes,
+                                     (size_t)s.B * s.Hkv * s.Lk * s.d, s.dtype, st) != hipSuccess)
+            return FLASHD_E_HIP;
+        k = base;
+        v = base + kv_bytes;
+        score_scale = scale * k8.kscale;       // one fp32 product, as in the decode kernel
+        out_scale = k8.vscale;
+        kv8_kernel = false;
     }
 
     Problem p;
@@ -180,7 +197,8 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.dtype = s.dtype;
     p.causal = causal != 0;
     p.splits = sp;
-    p.scale = scale;
+    p.scale = score_scale;
+    p.oscale = out_scale;
     p.shift = sa.on ? sa.shift : s.Lk - s.Lq;
     p.partial = (sp > 1 || sa.on) ? 1 : 0;
     p.store_o = p.partial ? 0 : 1;
@@ -195,11 +213,10 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
         p.from_state = sa.in != nullptr ? 1 : 0;
         p.ws = sa.out;
     }
-    p.kv8 = k8.on ? 1 : 0;
+    p.kv8 = kv8_kernel ? 1 : 0;
     p.kscale = k8.kscale;
     p.vscale = k8.vscale;
     if (direct && !in_kernel) p.ws = sa.out;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     const bool online = var == FLASHD_VARIANT_ONLINE_SOFTMAX;
     if (var == FLASHD_VARIANT_PER_KEY) e = flashd::launch_perkey(p, st);
@@ -278,7 +295,7 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.state_in = nullptr;
     p.state_out = nullptr;
     p.kv8 = 0;
-    p.kscale = p.vscale = 1.0f;
+    p.kscale = p.vscale = p.oscale = 1.0f;
     const hipError_t e =
         flashd::launch_skip_stats(p, lo, hi, counts, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;

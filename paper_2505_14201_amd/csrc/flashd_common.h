@@ -27,6 +27,7 @@ struct Problem {
     int from_state;     // 1: the tile kernel starts every row from state_in (no merge needed)
     int kv8;            // 1: k and v hold fp8 (e4m3) elements, scaled by kscale / vscale
     float kscale, vscale;
+    float oscale;       // factor on the output (and on the o of partial states); 1 unless kv8
     const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32
     float* state_out;        // optional state after this call's keys, same layout
 };

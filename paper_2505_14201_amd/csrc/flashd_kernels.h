@@ -27,6 +27,10 @@ hipError_t launch_decode(const Problem& p, bool online, hipStream_t st);
 bool decode_applies(int Hq, int Hkv, int Lq);
 long decode_workgroups(int B, int Hkv);
 
+// fp8 (e4m3) K and V of `elements` elements each -> storage type `dtype` (1 f16, 2 bf16), exact.
+hipError_t launch_widen_fp8(const void* k8, const void* v8, void* k, void* v, size_t elements,
+                            int dtype, hipStream_t st);
+
 // Static skip statistics of Sec. III-C: counts[0..2] = steps, steps with a score difference
 // <= lo, steps with one >= hi (overwritten).  Uses p.q, p.k and the shape only.
 hipError_t launch_skip_stats(const Problem& p, float lo, float hi, unsigned long long* counts,

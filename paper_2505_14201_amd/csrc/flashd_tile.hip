@@ -540,6 +540,7 @@ void tile_kernel(Problem p, TileSched sc) {
         asm volatile("" : "+v"(elane));
         const int col = elane & 31;
         const int hh = elane >> 5;
+        fin *= p.oscale;
         if (p.store_o) {
             // Stage the wavefront's 32 x D output block through LDS so that the global
             // stores are 16 bytes per lane and whole rows are contiguous.  Slot 1 is idle

@@ -64,9 +64,27 @@ def test_scales_that_are_not_powers_of_two_and_every_fp8_code():
     check(og.cpu(), ref, torch.bfloat16, "all codes")
 
 
-def test_fp8_entry_point_rejects_what_it_does_not_serve():
-    q = torch.zeros(1, 64, 64, 64, dtype=torch.bfloat16, device="cuda")     # 64 rows per kv head
+# prefill shapes: K and V are widened into scratch memory first, then the tile kernel runs
+PREFILL = [(1, 4, 2, 200, 333, 128), (2, 2, 2, 333, 200, 64), (1, 8, 8, 130, 130, 128),
+           (1, 2, 1, 64, 2000, 64)]
+
+
+@pytest.mark.parametrize("shape", PREFILL)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_fp8_kv_prefill_matches_the_oracle(shape, causal, dtype):
+    B, Hq, Hkv, Lq, Lk, d = shape
+    w = synthetic.small("kv8p", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=850 + Lq + Lk)
+    got, ref = run_and_ref(w, 0.03, 0.045)
+    check(got, ref, DT[dtype], f"{shape} causal={causal} {dtype}")
+
+
+def test_fp8_entry_point_rejects_fp32_queries():
+    q = torch.zeros(1, 4, 1, 64, dtype=torch.float32, device="cuda")
     k8 = torch.zeros(1, 1, 64, 64, dtype=torch.float8_e4m3fn, device="cuda")
-    with pytest.raises(flashd.FlashdError) as e:
+    with pytest.raises(ValueError):
         flashd.attn_fwd_kv8(q, k8, k8, torch.empty_like(q), False, 1.0, 1.0, 1.0)
-    assert e.value.status == -10
+    rc = flashd.raw().flashd_attn_fwd_kv8(q.data_ptr(), k8.data_ptr(), k8.data_ptr(),
+                                          q.data_ptr(), 1, 4, 1, 1, 64, 64, 0, 1.0, 1.0, 1.0,
+                                          flashd.F32, None)
+    assert rc == -10
