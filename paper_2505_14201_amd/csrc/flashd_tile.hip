@@ -104,6 +104,8 @@ __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg
         const char* vt = reinterpret_cast<const char*>(vg + (size_t)j0 * D);
         // The empty asm keeps the 32-bit offsets from being widened outside the loop, so
         // that each copy is one instruction with a scalar base and a 32-bit lane offset.
+        // (the immediate offset is a 13-bit signed field: 1024 N must stay below 4096)
+        static_assert(1024 * (NI - 1) < 4096, "immediate offset of the copy out of range");
         auto issue = [&](auto n) {
             constexpr int N = decltype(n)::value;
             uint32_t off = dl.koff[N];
@@ -605,12 +607,13 @@ void tile_kernel(Problem p, TileSched sc) {
 constexpr int kXcds = 8;
 constexpr int kCusPerXcd = 32;
 
-// resident workgroups per compute unit of one kernel instantiation (asked once)
-template <typename K>
-static int resident_per_cu(K kernel) {
-    static const int n = [kernel] {
+// resident workgroups per compute unit of one kernel instantiation (asked once per kernel:
+// the kernel is a template argument, so each has its own cached answer)
+template <auto Kernel>
+static int resident_per_cu() {
+    static const int n = [] {
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kNW * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, Kernel, kNW * 64, 0) != hipSuccess ||
             nb < 1)
             nb = 1;
         return nb;
@@ -642,8 +645,8 @@ template <typename T, int D>
 static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
     const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
     if (m_tiles * p.splits * p.B * p.Hq > 0x7fffffffL) return hipErrorInvalidValue;
-    const int per_cu = online ? resident_per_cu(tile_kernel<T, D, true>)
-                              : resident_per_cu(tile_kernel<T, D, false>);
+    const int per_cu = online ? resident_per_cu<tile_kernel<T, D, true>>()
+                              : resident_per_cu<tile_kernel<T, D, false>>();
     const TileSched sc = tile_sched(p, per_cu * kCusPerXcd);
     // One workgroup per virtual workgroup, handed out by the hardware as slots free up.
     // (The kernel can also walk several virtual workgroups per workgroup, but a fixed split
