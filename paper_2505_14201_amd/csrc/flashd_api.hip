@@ -112,9 +112,14 @@ int cached_workspace(void* stream, size_t bytes, void** out) {
     std::lock_guard<std::mutex> lk(g_mu);
     CacheEntry& e = g_cache[std::make_pair(dev, stream)];
     if (e.bytes < bytes) {
+        // grow geometrically; if that much is not to be had, take exactly what is needed
         size_t want = e.bytes * 2 > bytes ? e.bytes * 2 : bytes;
         void* p = nullptr;
-        if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+        if (hipMalloc(&p, want) != hipSuccess) {
+            (void)hipGetLastError();
+            want = bytes;
+            if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+        }
         e.ptr = p;
         e.bytes = want;
     }
