@@ -578,8 +578,11 @@ void tile_kernel(Problem p, TileSched sc) {
                 const uint16_t* src = (r < 16 ? stage_k : stage_k + 2 * kTile) +
                                       (r & 15) * D + 8 * (c ^ (r % C::CPR));
                 const u32x4 x = *reinterpret_cast<const u32x4*>(src);
+                // written once and not read again by this launch: a streaming store, so
+                // that the output does not push K and V out of the caches
                 if (cur.wrow0 + r < p.Lq)
-                    *reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
+                    __builtin_nontemporal_store(
+                        x, reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c));
             }
         }
         if (p.partial && cur.wrow0 + col < p.Lq) {
