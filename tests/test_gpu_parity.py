@@ -48,6 +48,27 @@ def test_small_shapes_half(shape, causal, d, dtype, variant):
     check(got, ref, DT[dtype], f"{shape} causal={causal} d={d} {dtype} variant={variant}")
 
 
+@pytest.mark.parametrize("scale", [-0.11, 0.0])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (ONLINE, "f16"), (PER_KEY, "f32"),
+                                           (TILE, "f16")])
+def test_negative_and_zero_scale(scale, causal, variant, dtype):
+    """The boundary takes any scale: a negative one turns the ranking of the keys round, zero
+    makes every visible key weigh the same; masks and ragged tiles must not care."""
+    w = synthetic.small("t", 1, 4, 2, 200, 333, 128, dtype, causal, seed=77)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, scale)
+    for splits in (1, 3):
+        got = run_flashd(q, k, v, causal, scale, variant, splits)
+        check(got, ref, DT[dtype], f"scale={scale} causal={causal} {dtype} variant={variant} "
+                                   f"splits={splits}")
+    # decode shape (the split-K decode kernel)
+    wd = synthetic.small("t", 2, 8, 2, 1, 300, 128, dtype, False, seed=78)
+    q, k, v, _ = synthetic.make_qkv(wd)
+    got = run_flashd(q, k, v, False, scale, variant, 2)
+    check(got, oracle(q, k, v, False, scale), DT[dtype], f"decode scale={scale} {dtype}")
+
+
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("d", [64, 128])
