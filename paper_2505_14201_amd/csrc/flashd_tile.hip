@@ -87,6 +87,17 @@ template <int D> struct DmaLane {
 
 template <int N> struct IntC { static constexpr int value = N; };
 
+// Wait until every global->LDS copy (and load) this wavefront has issued is complete.  The
+// builtin rather than inline assembly, so that the compiler's own bookkeeping of outstanding
+// copies sees the wait: after an assembly wait it still assumed copies in flight and put a
+// full wait of its own before the first LDS write of the epilogue, which then also waited
+// for the Q fragments just requested for the next row tile.
+__device__ __forceinline__ void wait_copies() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), the other counters not waited for
+    asm volatile("" ::: "memory");
+}
+
+
 // Start the copy of the K and V tiles whose first key is j0 into ks / vs (the wavefront
 // fills its own 16 rows of each).  A tile that sticks out past the last key takes the slow
 // form with rows clamped to the last key (masked later).
@@ -142,7 +153,8 @@ __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg
 // flashd_mma.h for the lane roles); vaddr = this lane's element offset for the d-block,
 // key0 = first key of the 16-key group.
 template <int D>
-__device__ __forceinline__ u32x4 tile_v_operand(const uint16_t* vs, int vaddr, int key0) {
+__device__ __forceinline__ u32x4 tile_v_operand(const uint16_t* __restrict__ vs, int vaddr,
+                                                int key0) {
     typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(vs + vaddr + key0 * D));
     const s16x4 hi =
@@ -480,12 +492,17 @@ void tile_kernel(Problem p, TileSched sc) {
                     }
                 g.st = {lam_in * kLog2e, 1.0f, 1.0f};
             }
+            // Have the state here before going on: left pending, these loads make the
+            // compiler put a full wait in front of the epilogue's first use of U (a row tile
+            // without key tiles gets there with no matrix instruction in between), and that
+            // wait then also covers the Q fragments requested for the next row tile.
+            wait_copies();
         }
 
         if (!have0 && cur.n > 0)
             tile_copy<D>(cur.kg, cur.vg, cur.jbase, p.Lk, dl, wave, lane, lds, lds + 2 * kTile);
         if (first || !have0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_copies();
             __syncthreads();
         }
         have0 = false;
@@ -510,7 +527,7 @@ void tile_kernel(Problem p, TileSched sc) {
             if (j0 < cur.wmax)
                 tile_math<T, D, ONLINE, PAR>(lds, g, j0, hh, lane, nvis,
                                              t == 0 || j0 + kBC > cur.wmin, c_log2);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_copies();
             __syncthreads();
         };
         for (int t = 0; t < cur.n; t += 2) {
