@@ -21,8 +21,9 @@
  *   - B, Hq, Hkv, Lq, Lk >= 1; Hq % Hkv == 0; d is 64 or 128.
  *   - causal != 0: key j is visible to query i iff j <= i + (Lk - Lq) (the last query sees
  *     every key).  A query row with no visible key yields zeros.  causal == 0: all keys.
- *   - `scale` multiplies the dot product in fp32.  State and accumulation are fp32 for all
- *     storage types.
+ *   - `scale` multiplies the dot product in fp32; any finite value is taken as it is (zero
+ *     weighs every visible key the same, a negative one turns the ranking of the keys
+ *     round).  State and accumulation are fp32 for all storage types.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work and return; they do not synchronise.
  *   - Every function returns a flashd_status (0 = success, negative = error).  On an error
