@@ -48,6 +48,24 @@ def test_small_shapes_half(shape, causal, d, dtype, variant):
     check(got, ref, DT[dtype], f"{shape} causal={causal} d={d} {dtype} variant={variant}")
 
 
+@pytest.mark.parametrize("shape,causal,variant,splits", [
+    ((1, 8, 1, 1, 300001), False, TILE, 0),        # decode kernel, automatic splits, ragged tail
+    ((1, 8, 1, 1, 300001), False, TILE, 64),       # the most splits the boundary takes
+    ((1, 2, 1, 130, 200003), True, TILE, 0),       # tile kernel, Lk >> Lq, bottom-right mask
+    ((1, 2, 1, 130, 200003), False, ONLINE, 7),
+    ((1, 1, 1, 3, 100000), True, PER_KEY, 0),
+])
+def test_very_long_key_ranges(shape, causal, variant, splits):
+    """Hundreds of thousands of keys per row (thousands of key tiles, ragged last tile): the
+    carried state has to stay accurate over the whole run."""
+    B, Hq, Hkv, Lq, Lk = shape
+    w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, 64, "bf16", causal, seed=4242 + Lk)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, w.scale)
+    got = run_flashd(q, k, v, causal, w.scale, variant, splits)
+    check(got, ref, torch.bfloat16, f"{shape} causal={causal} variant={variant} splits={splits}")
+
+
 @pytest.mark.parametrize("scale", [-0.11, 0.0])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (ONLINE, "f16"), (PER_KEY, "f32"),
