@@ -592,18 +592,30 @@ void tile_kernel(Problem p, TileSched sc) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // all reads of the staged block first, then the stores: one read-wait-store
+            // chain per row group leaves the wavefront waiting on LDS eight times in a row
+            constexpr int NST = 32 * C::CPR / 64;
+            u32x4 xs[NST];
 #pragma unroll
-            for (int n = 0; n < 32 * C::CPR / 64; ++n) {
+            for (int n = 0; n < NST; ++n) {
                 const int slot = n * 64 + elane;
                 const int r = slot / C::CPR;                // output row within the wavefront
                 const int c = slot % C::CPR;
                 const uint16_t* src = (r < 16 ? stage_k : stage_k + 2 * kTile) +
                                       (r & 15) * D + 8 * (c ^ (r % C::CPR));
-                const u32x4 x = *reinterpret_cast<const u32x4*>(src);
-                // (a plain store: a streaming one is 0.5-1 % faster here but makes the memory
-                // side fetch as many bytes again as it writes)
+                xs[n] = *reinterpret_cast<const u32x4*>(src);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NST; ++n) {
+                const int slot = n * 64 + elane;
+                const int r = slot / C::CPR;
+                const int c = slot % C::CPR;
+                // written once and not read again by this launch: streaming stores
                 if (cur.wrow0 + r < p.Lq)
-                    *reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c) = x;
+                    __builtin_nontemporal_store(
+                        xs[n],
+                        reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c));
             }
         }
         if (p.partial && cur.wrow0 + col < p.Lq) {
