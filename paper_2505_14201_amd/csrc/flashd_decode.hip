@@ -199,10 +199,16 @@ void decode_kernel(Problem p) {
         u32x4 bfrag[2];
         if (!ONLINE) {
             bool risky;
-            if (general) risky = lazy_spec_pack<T, 1, true, true>(acc, bfrag, st, c_log2, jb, nvis, lane);
-            else risky = lazy_spec_pack<T, 1, false, false>(acc, bfrag, st, c_log2, jb, nvis, lane);
+            LazySpec spec;
+            if (general) risky = lazy_spec_pack<T, 1, true, true>(acc, bfrag, st, c_log2, jb, nvis, lane, spec);
+            else risky = lazy_spec_pack<T, 1, false, false>(acc, bfrag, st, c_log2, jb, nvis, lane, spec);
             if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-                const float f = lazy_redo_pack<T, 1>(acc, bfrag, st, risky, c_log2, general, jb, nvis);
+                const bool lost = risky && !(spec.psum <= kLazyShiftMax);
+                float f;
+                if (__builtin_amdgcn_ballot_w64(lost) != 0)
+                    f = lazy_redo_pack<T, 1>(acc, bfrag, st, risky, c_log2, general, jb, nvis);
+                else
+                    f = lazy_shift_pack<T, 1>(acc, bfrag, st, risky, spec, c_log2, general, jb, nvis);
 #pragma unroll
                 for (int i = 0; i < NDB; ++i)
 #pragma unroll

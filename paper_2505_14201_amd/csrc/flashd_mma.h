@@ -115,14 +115,29 @@ __device__ __forceinline__ u32x4 lds_read_v_operand(const uint16_t* base, int ro
 //
 // lazy_spec_pack() does that speculatively, branch-free, leaving the raw scores untouched,
 // and reports rows whose psum left the safe range (some 2^{s_j - R} too large for the
-// storage type: a score far above everything before it).  For those rows lazy_redo_pack()
-// redoes the tile from the raw scores with the key-by-key sigmoid recurrence, which
-// saturates instead of overflowing, and moves R.
+// storage type: a score far above everything before it).  If that psum is still an ordinary
+// fp32 number the tile's total is known and only the coefficients do not fit:
+// lazy_shift_pack() moves the row's reference up by a power of two and rounds the
+// coefficients again.  If psum itself overflowed, lazy_redo_pack() redoes the tile from the
+// raw scores with the key-by-key sigmoid recurrence, which saturates instead of overflowing,
+// and moves R.
 struct LazyRow {
     float R;      // exponent reference, log2 units
     float beta;   // o = beta * U
     float one;    // 0.0f while the row is empty, then 1.0f
 };
+
+// What the speculative pass found for a row: the sum of its coefficients and the reference
+// they were taken against (the row's R, or the tile's first visible score for an empty row).
+struct LazySpec {
+    float psum;
+    float ref;
+};
+
+// psum above this is treated as overflowed.  Below it one + beta psum (beta <= 2) stays far
+// under 2^126, so that its reciprocal is still a normal number (v_rcp_f32 returns zero where
+// the result would be subnormal, and a beta of zero would poison the row).
+constexpr float kLazyShiftMax = 1.0e30f;      // ~2^100
 
 template <typename T> struct LazyLimit;
 template <> struct LazyLimit<BF16> { static constexpr float kMaxPsum = 1.0e18f; };   // ~2^60
@@ -152,7 +167,7 @@ __device__ __forceinline__ float pair_low(float x) {
 template <typename T, int NB, bool MASK, bool MAY_BE_EMPTY>
 __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
                                                LazyRow& st, float c_log2, int jb, int nvis,
-                                               int lane) {
+                                               int lane, LazySpec& spec) {
     const float ninf = -__builtin_inff();
     bool empty = false;
     float ref = st.R;
@@ -182,6 +197,8 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
         __builtin_amdgcn_sched_barrier(0);
     }
     psum = pair_sum(psum);
+    spec.psum = psum;
+    spec.ref = ref;
     const bool safe = psum <= LazyLimit<T>::kMaxPsum;             // false for inf and NaN
     if (MAY_BE_EMPTY) {
         const bool upd = safe & !(empty & (psum == 0.0f));
@@ -195,6 +212,51 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
         st.beta = safe ? nb : st.beta;
     }
     return !safe;
+}
+
+// Middle path, entered by the whole wavefront when some row is risky and every risky row's
+// psum is an ordinary number.  For a risky row the update of the state is the one of the
+// common path (tot = one + beta psum); its reference moves up by e = exponent of psum
+// (psum = m 2^e, 1/2 <= m < 1), so that every coefficient 2^{s_j - R - e} <= m < 1 fits the
+// storage type; what the row holds shrinks with it, U by 2^-e (the returned factor) and beta
+// by 2^e the other way, o = beta U unchanged.  The other rows' coefficients are formed again
+// with the reference they used (same values).  No maximum is taken and no key is looked at
+// on its own.
+template <typename T, int NB>
+__device__ __forceinline__ float lazy_shift_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                                 LazyRow& st, bool risky, const LazySpec& spec,
+                                                 float c_log2, bool need_mask, int jb, int nvis) {
+    const float ninf = -__builtin_inff();
+    float f = 1.0f;
+    float ref = st.R;     // rows that were not risky: the reference lazy_spec_pack used
+    if (risky) {
+        const int e = __builtin_amdgcn_frexp_expf(spec.psum);
+        const bool empty = st.one == 0.0f;
+        const float tot = fmaf(st.beta, spec.psum, st.one);
+        const float nb = st.beta * __builtin_amdgcn_rcpf(tot);       // below 2^-e, then scaled up
+        st.beta = __builtin_ldexpf(nb, e);
+        ref = spec.ref + (float)e;
+        st.R = ref;
+        st.one = 1.0f;
+        f = empty ? 0.0f : __builtin_ldexpf(1.0f, -e);
+    }
+    int nv = nvis;
+    asm volatile("" : "+v"(nv));      // see lazy_redo_pack
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+        f32x8 pv;
+#pragma unroll
+        for (int e8 = 0; e8 < 8; ++e8) {
+            const int r = 8 * (g & 1) + e8;
+            float x = fmaf(acc[g >> 1][r], c_log2, -ref);
+            const bool masked = need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv;
+            if (masked) x = ninf;
+            pv[e8] = exp2_fast(x);
+        }
+        bfrag[g] = Mma<T>::pack8(pv);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return f;
 }
 
 // Rare path, entered by the whole wavefront when any of its rows is risky.  Key-by-key

@@ -221,18 +221,28 @@ __device__ __forceinline__ void phase_coeffs(const uint16_t* ks, const f32x16 (&
     const int jb = j0 + 4 * hh;
     if (!ONLINE) {
         bool risky;
+        LazySpec spec;
         if (general)
-            risky = lazy_spec_pack<T, 2, true, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
+            risky = lazy_spec_pack<T, 2, true, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane,
+                                                     spec);
         else
-            risky = lazy_spec_pack<T, 2, false, false>(acc, bfrag, g.st, c_log2, jb, nvis, lane);
+            risky = lazy_spec_pack<T, 2, false, false>(acc, bfrag, g.st, c_log2, jb, nvis, lane,
+                                                       spec);
         if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // rare: flagged rows redo the tile with the key-by-key sigmoid recurrence.  The
+            // rare: a flagged row's coefficients do not fit the storage type.  Its reference
+            // moves up by a power of two (psum still a number), or, where psum itself
+            // overflowed, the rows redo the tile with the key-by-key sigmoid recurrence.  The
             // raw scores are formed again (K is still in LDS) rather than kept: holding them
             // until here would cost the common path 32 registers.
             f32x16 acc2[2];
             phase_scores<T, D>(ks, g, acc2);
-            const float f =
-                lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
+            const bool lost = risky && !(spec.psum <= kLazyShiftMax);
+            float f;
+            if (__builtin_amdgcn_ballot_w64(lost) != 0)
+                f = lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
+            else
+                f = lazy_shift_pack<T, 2>(acc2, bfrag, g.st, risky, spec, c_log2, general, jb,
+                                          nvis);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
