@@ -209,6 +209,35 @@ def test_huge_scores_and_dominant_keys_stay_finite_and_right(variant, dtype, d, 
           smax=max_abs_score(q, k, w.scale))
 
 
+@pytest.mark.parametrize("dtype,step_nats", [("f16", 12.0), ("f16", 30.0), ("bf16", 45.0),
+                                             ("bf16", 60.0), ("bf16", 90.0), ("f16", 90.0)])
+@pytest.mark.parametrize("Lq", [1, 160])
+def test_staircase_scores(dtype, step_nats, Lq):
+    """Scores that climb in steps every 96 keys: each step lifts the scores by step_nats above
+    everything before it -- past what the rounded coefficients can hold (2^14 for f16, 2^60 for
+    bf16, in powers of two; a nat is 1.44 of them) but, for the smaller steps, not past fp32,
+    which is the case the reference shift serves; the largest steps overflow fp32 as well.
+    The keys of a level share the weight, so the result is the mean of that level's values
+    (plus a little of the level below), not a single key."""
+    Lk, d = 96 * 6 + 40, 64
+    rng = np.random.default_rng(int(step_nats) + Lq)
+    level = (np.arange(Lk) // 96).astype(np.float64)
+    q = torch.zeros(1, 2, Lq, d)
+    q[..., 0] = 1.0
+    q[..., 1:] = torch.from_numpy(0.05 * rng.standard_normal((1, 2, Lq, d - 1))).float()
+    k = torch.from_numpy(0.5 * rng.standard_normal((1, 1, Lk, d))).float()
+    k[0, 0, :, 0] = torch.from_numpy(step_nats * level).float()
+    v = torch.from_numpy(rng.standard_normal((1, 1, Lk, d))).float()
+    qq, kk, vv = (t.to(DT[dtype]) for t in (q, k, v))
+    for causal in (False, True):
+        ref = oracle(qq, kk, vv, causal, 1.0)
+        for variant, splits in ((TILE, 1), (TILE, 2), (PER_KEY, 1)):
+            got = run_flashd(qq, kk, vv, causal, 1.0, variant, splits)
+            check(got, ref, DT[dtype], f"staircase {dtype} step={step_nats} Lq={Lq} "
+                                       f"causal={causal} variant={variant} splits={splits}",
+                  smax=max_abs_score(qq, kk, 1.0))
+
+
 def test_score_ramps():
     """s_j = +-c*j: an ascending ramp keeps only the last key, a descending one the first."""
     L, d = 200, 64
