@@ -17,6 +17,7 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -36,6 +37,25 @@ template <> struct Mma<BF16> {
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, bf16x8));
     }
+    // Sum of the 8 coefficients of a group.  bf16: of the ROUNDED coefficients, two per
+    // v_dot2c_f32_bf16 with a pair of ones (one rounding per instruction): half the
+    // instructions of adding the fp32 values, and the sum that normalises a row is the sum of
+    // exactly the weights the output product uses, so a weight of nearly 1 carries no
+    // rounding error of its own into the output.
+    static __device__ __forceinline__ void sum8(const f32x8& x, u32x4 packed, f32x4& acc) {
+        (void)x;
+        // the pair of ones in a scalar register rather than as a 32-bit literal in each of
+        // the instructions
+        unsigned one_bits = 0x3f803f80u;
+        asm volatile("" : "+s"(one_bits));
+        const bf16x2 ones = __builtin_bit_cast(bf16x2, one_bits);
+        const bf16x8 v = __builtin_bit_cast(bf16x8, packed);
+        // four independent chains: one long one would wait on every instruction's latency
+        acc[0] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 0, 1), ones, acc[0], false);
+        acc[1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 2, 3), ones, acc[1], false);
+        acc[2] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 4, 5), ones, acc[2], false);
+        acc[3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 6, 7), ones, acc[3], false);
+    }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, bf16x4));
     }
@@ -54,6 +74,13 @@ template <> struct Mma<F16> {
     }
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, f16x8));
+    }
+    // fp16: of the fp32 values (a coefficient beyond the fp16 range must still give a finite
+    // sum, which the reference-shift path works from; fp16 rounding is eight times finer)
+    static __device__ __forceinline__ void sum8(const f32x8& x, u32x4 packed, f32x4& acc) {
+        (void)packed;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[0] += x[e];
     }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, f16x4));
@@ -178,7 +205,7 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
         const float ref0 = ((jb - 4 * (lane >> 5)) < nvis) ? s0 : 0.0f;
         ref = empty ? ref0 : st.R;
     }
-    float psum = 0.0f;
+    f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -188,15 +215,15 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
             float x = fmaf(acc[g >> 1][r], c_log2, -ref);
             if (MASK) x = ((jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis) ? ninf : x;
             pv[e] = exp2_fast(x);
-            psum += pv[e];
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        Mma<T>::sum8(pv, bfrag[g], ps4);
         // Keep the groups apart: scheduled together, the 32 exponents and 32 results of a
         // tile are all live at once, and the register allocator then starts to move the
         // accumulators around.  Eight independent elements are enough to hide latencies.
         __builtin_amdgcn_sched_barrier(0);
     }
-    psum = pair_sum(psum);
+    float psum = pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
     spec.psum = psum;
     spec.ref = ref;
     const bool safe = psum <= LazyLimit<T>::kMaxPsum;             // false for inf and NaN
@@ -344,7 +371,7 @@ __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bf
     const float m_new = fmaxf(m, mx);
     const float m_use = (m_new == ninf) ? 0.0f : m_new;
     const float resc = exp2_fast(m - m_use);
-    float psum = 0.0f;
+    f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -354,12 +381,12 @@ __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bf
             float x = fmaf(acc[g >> 1][r], c_log2, -m_use);
             if (MASK && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
             pv[e] = exp2_fast(x);
-            psum += pv[e];
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        Mma<T>::sum8(pv, bfrag[g], ps4);
         __builtin_amdgcn_sched_barrier(0);
     }
-    psum = pair_sum(psum);
+    const float psum = pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
     l = l * resc + psum;
     m = m_new;
     return resc;
