@@ -25,6 +25,8 @@
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
 
+#include <type_traits>
+
 namespace flashd {
 
 constexpr int kDecWaves = 4;
@@ -207,6 +209,8 @@ void decode_kernel(Problem p) {
                 float f;
                 if (__builtin_amdgcn_ballot_w64(lost) != 0)
                     f = lazy_redo_pack<T, 1>(acc, bfrag, st, risky, c_log2, general, jb, nvis);
+                else if (std::is_same<T, BF16>::value)
+                    f = lazy_shift_inplace_bf16(bfrag, 2, st, risky, spec);
                 else
                     f = lazy_shift_pack<T, 1>(acc, bfrag, st, risky, spec, c_log2, general, jb, nvis);
 #pragma unroll

@@ -37,6 +37,7 @@ template <> struct Mma<BF16> {
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, bf16x8));
     }
+    static constexpr bool kRoundedSum = true;
     // Sum of the 8 coefficients of a group.  bf16: of the ROUNDED coefficients, two per
     // v_dot2c_f32_bf16 with a pair of ones (one rounding per instruction): half the
     // instructions of adding the fp32 values, and the sum that normalises a row is the sum of
@@ -75,6 +76,7 @@ template <> struct Mma<F16> {
     static __device__ __forceinline__ u32x4 pack8(f32x8 x) {
         return __builtin_bit_cast(u32x4, __builtin_convertvector(x, f16x8));
     }
+    static constexpr bool kRoundedSum = false;
     // fp16: of the fp32 values (a coefficient beyond the fp16 range must still give a finite
     // sum, which the reference-shift path works from; fp16 rounding is eight times finer)
     static __device__ __forceinline__ void sum8(const f32x8& x, u32x4 packed, f32x4& acc) {
@@ -286,6 +288,42 @@ __device__ __forceinline__ float lazy_shift_pack(const f32x16 (&acc)[NB], u32x4 
     return f;
 }
 
+// The same middle path where the coefficients of the speculative pass are still at hand and
+// have the range of fp32 (bf16): they are not formed again but scaled by 2^-e as they are,
+// by taking e off the exponent field of each (two per instruction, saturating at zero), so
+// that the coefficients the output product uses are bit for bit the ones whose sum went into
+// the state (formed again at the new reference, one that sat on a rounding boundary could
+// land on the other side).  Needs neither the raw scores nor an exponential.
+__device__ __forceinline__ float lazy_shift_inplace_bf16(u32x4* bfrag, int ngroups, LazyRow& st,
+                                                         bool risky, const LazySpec& spec) {
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    float f = 1.0f;
+    unsigned sub = 0u;                   // e in the position of the bf16 exponent field
+    if (risky) {
+        const int e = __builtin_amdgcn_frexp_expf(spec.psum);
+        const bool empty = st.one == 0.0f;
+        const float tot = fmaf(st.beta, spec.psum, st.one);
+        const float nb = st.beta * __builtin_amdgcn_rcpf(tot);       // below 2^-e, then scaled up
+        st.beta = __builtin_ldexpf(nb, e);
+        st.R = spec.ref + (float)e;
+        st.one = 1.0f;
+        f = empty ? 0.0f : __builtin_ldexpf(1.0f, -e);
+        sub = (unsigned)e << 7;          // 0 < e <= 100: fits the field
+    }
+    // (whole vectors: a bit cast of a single vector element to a pair came out of this
+    // compiler reading element 0 every time)
+    const unsigned short s1 = (unsigned short)sub;
+    const u16x8 s8 = {s1, s1, s1, s1, s1, s1, s1, s1};
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if (g < ngroups) {
+            const u16x8 x = __builtin_bit_cast(u16x8, bfrag[g]);
+            bfrag[g] = __builtin_bit_cast(u32x4, __builtin_elementwise_sub_sat(x, s8));
+        }
+    }
+    return f;
+}
+
 // Rare path, entered by the whole wavefront when any of its rows is risky.  Key-by-key
 // recurrence inside the lane over the raw scores: Lam_j = Lam_{j-1} + softplus(s_j -
 // Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the
@@ -321,15 +359,16 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
     const bool none = risky && lam_new == ninf;
     float f = 1.0f;
     float ref = st.R;     // rows that were not risky: the reference lazy_spec_pack used
+    float w_old = 0.0f;   // 1 - W = 2^{Lam_old - Lam_new}: what is left of the old state
     if (risky) {
         ref = none ? 0.0f : lam_new;
-        // the old state decays by 1 - W = 2^{Lam_old - Lam_new}; it is applied to U now
-        f = empty ? 0.0f : st.beta * exp2_fast(lam_old - lam_new);
-        st.beta = 1.0f;
+        w_old = empty ? 0.0f : exp2_fast(lam_old - lam_new);
+        f = st.beta * w_old;            // applied to U now
         st.R = ref;
         st.one = none ? 0.0f : 1.0f;
     }
     asm volatile("" : "+v"(nv2));
+    f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -343,7 +382,16 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
             pv[e] = exp2_fast(x);
         }
         bfrag[g] = Mma<T>::pack8(pv);
+        if (Mma<T>::kRoundedSum) Mma<T>::sum8(pv, bfrag[g], ps4);
         __builtin_amdgcn_sched_barrier(0);
+    }
+    if (risky) {
+        // Exactly, w_old and the tile's coefficients sum to one and beta is 1.  Where the row
+        // sums are those of the rounded coefficients (Mma::sum8) beta takes the sum they
+        // really have, so that o = beta U stays a weighted mean of the values.
+        float tot = 1.0f;
+        if (Mma<T>::kRoundedSum) tot = w_old + pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
+        st.beta = (none || !Mma<T>::kRoundedSum) ? 1.0f : __builtin_amdgcn_rcpf(tot);
     }
     return f;
 }

@@ -234,15 +234,20 @@ __device__ __forceinline__ void phase_coeffs(const uint16_t* ks, const f32x16 (&
             // overflowed, the rows redo the tile with the key-by-key sigmoid recurrence.  The
             // raw scores are formed again (K is still in LDS) rather than kept: holding them
             // until here would cost the common path 32 registers.
-            f32x16 acc2[2];
-            phase_scores<T, D>(ks, g, acc2);
             const bool lost = risky && !(spec.psum <= kLazyShiftMax);
+            const bool any_lost = __builtin_amdgcn_ballot_w64(lost) != 0;
             float f;
-            if (__builtin_amdgcn_ballot_w64(lost) != 0)
-                f = lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
-            else
-                f = lazy_shift_pack<T, 2>(acc2, bfrag, g.st, risky, spec, c_log2, general, jb,
-                                          nvis);
+            if (std::is_same<T, BF16>::value && !any_lost) {
+                f = lazy_shift_inplace_bf16(bfrag, 4, g.st, risky, spec);
+            } else {
+                f32x16 acc2[2];
+                phase_scores<T, D>(ks, g, acc2);
+                if (any_lost)
+                    f = lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
+                else
+                    f = lazy_shift_pack<T, 2>(acc2, bfrag, g.st, risky, spec, c_log2, general,
+                                              jb, nvis);
+            }
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
