@@ -18,7 +18,8 @@
  *     frees or keeps them beyond the work it enqueues.  They must be 16-byte aligned.
  *   - Layout, row-major and contiguous: q, o: [B][Hq][Lq][d];  k, v: [B][Hkv][Lk][d];
  *     all four in the storage type named by `dtype`.  o must not overlap an input.
- *   - B, Hq, Hkv, Lq, Lk >= 1; Hq % Hkv == 0; d is 64 or 128.
+ *   - B, Hq, Hkv, Lq, Lk >= 1; Hq % Hkv == 0; d is 64 or 128.  B and Hq are at most 65535,
+ *     Lq and Lk at most 10^9 and a tensor has at most 10^12 elements (else FLASHD_E_SHAPE).
  *   - causal != 0: key j is visible to query i iff j <= i + (Lk - Lq) (the last query sees
  *     every key).  A query row with no visible key yields zeros.  causal == 0: all keys.
  *   - `scale` multiplies the dot product in fp32; any finite value is taken as it is (zero
@@ -44,7 +45,7 @@ typedef enum { FLASHD_F32 = 0, FLASHD_F16 = 1, FLASHD_BF16 = 2 } flashd_dtype;
 typedef enum {
     FLASHD_OK = 0,
     FLASHD_E_NULL = -1,       /* q, k, v or o is NULL                                   */
-    FLASHD_E_SHAPE = -2,      /* a dimension is < 1, or a size overflows                */
+    FLASHD_E_SHAPE = -2,      /* a dimension is < 1 or beyond the limits stated above   */
     FLASHD_E_DTYPE = -3,      /* dtype is not a flashd_dtype                            */
     FLASHD_E_HEADDIM = -4,    /* d is not 64 or 128                                     */
     FLASHD_E_GQA = -5,        /* Hq is not a multiple of Hkv                            */
@@ -118,7 +119,8 @@ int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
  *              storage type (what the state's o holds).  o and state_out must not both be NULL.
  *   causal_shift  with causal != 0, key j of THIS call is visible to query i iff
  *              j <= i + causal_shift; for a chunk that starts at key offset k0 of Lk_total
- *              keys that is (Lk_total - Lq) - k0.  Ignored when causal == 0.
+ *              keys that is (Lk_total - Lq) - k0.  Any int is valid (Lk or more shows every
+ *              key, less than -Lq none).  Ignored when causal == 0.
  * Other arguments, conventions and errors as for flashd_attn_fwd (all pointers 16-byte aligned).
  * Takes scratch memory for partial states from the same grow-only cache as flashd_attn_fwd.
  */

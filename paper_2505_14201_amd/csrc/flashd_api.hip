@@ -20,6 +20,8 @@ struct Shape { int B, Hq, Hkv, Lq, Lk, d, dtype; };
 int validate_shape(const Shape& s) {
     if (s.B < 1 || s.Hq < 1 || s.Hkv < 1 || s.Lq < 1 || s.Lk < 1) return FLASHD_E_SHAPE;
     if (s.B > 65535 || s.Hq > 65535) return FLASHD_E_SHAPE;          // grid y/z limits
+    // row and key indices, and their sums with the causal shift, are 32-bit in the kernels
+    if (s.Lq > 1000000000 || s.Lk > 1000000000) return FLASHD_E_SHAPE;
     if (s.dtype != FLASHD_F32 && s.dtype != FLASHD_F16 && s.dtype != FLASHD_BF16)
         return FLASHD_E_DTYPE;
     if (s.d != 64 && s.d != 128) return FLASHD_E_HEADDIM;
@@ -204,7 +206,10 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.splits = sp;
     p.scale = score_scale;
     p.oscale = out_scale;
-    p.shift = sa.on ? sa.shift : s.Lk - s.Lq;
+    // a shift of Lk or more shows every key and one below -Lq none: clamping the caller's
+    // value there changes no result and keeps i + shift inside 32 bits
+    const int shift_in = sa.shift > s.Lk ? s.Lk : (sa.shift < -s.Lq - 1 ? -s.Lq - 1 : sa.shift);
+    p.shift = sa.on ? shift_in : s.Lk - s.Lq;
     p.partial = (sp > 1 || sa.on) ? 1 : 0;
     p.store_o = p.partial ? 0 : 1;
     p.merge = p.partial;

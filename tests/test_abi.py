@@ -71,6 +71,8 @@ def test_shape_errors():
         assert fwd(**{name: -3}) == E_SHAPE
     assert fwd(B=70000) == E_SHAPE
     assert fwd(B=60000, Hq=60000, Hkv=60000, Lq=100000, Lk=8) == E_SHAPE   # element count overflow
+    assert fwd(B=1, Hq=1, Hkv=1, Lq=8, Lk=2_000_000_000, d=64) == E_SHAPE      # 32-bit key indices
+    assert fwd(B=1, Hq=1, Hkv=1, Lq=1_500_000_000, Lk=8, d=64) == E_SHAPE
 
 
 def test_dtype_headdim_gqa_align():

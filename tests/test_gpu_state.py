@@ -114,3 +114,27 @@ def test_dominant_keys_across_chunk_boundaries_stay_finite():
     o, st = run_chunks(q, k, v, True, w.scale, (100, 101, 300))
     assert torch.isfinite(o).all()
     check(o, ref[..., :64], torch.float16, "stress chunks")
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 200, 300, 128), (1, 8, 2, 2, 900, 64)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_extreme_causal_shifts_show_every_key_or_none(shape, dtype):
+    """Any int is a valid shift: from Lk up every key is visible (the non-causal result),
+    below -Lq none (zeros, the state of a row without keys)."""
+    B, Hq, Hkv, Lq, Lk, d = shape
+    w = synthetic.small("shift", B, Hq, Hkv, Lq, Lk, d, dtype, False, seed=930 + Lq)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oa.attn(q, k, v, False, w.scale)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    for shift in (Lk, Lk + 5, 2 ** 31 - 1):
+        o = torch.full_like(qg, float("nan"))
+        flashd.attn_fwd_state(qg, kg, vg, True, w.scale, o=o, causal_shift=shift)
+        torch.cuda.synchronize()
+        check(o.cpu(), ref, DT[dtype], f"{shape} {dtype} shift={shift}")
+    for shift in (-Lq, -Lq - 7, -2 ** 31):
+        o = torch.full_like(qg, float("nan"))
+        st = torch.full((B, Hq, Lq, d + 2), float("nan"), dtype=torch.float32, device="cuda")
+        flashd.attn_fwd_state(qg, kg, vg, True, w.scale, o=o, state_out=st, causal_shift=shift)
+        torch.cuda.synchronize()
+        assert torch.count_nonzero(o) == 0, f"shift={shift}: rows without keys must be zeros"
+        assert torch.isneginf(st[..., d] - st[..., d + 1]).all(), f"shift={shift}: empty state"
