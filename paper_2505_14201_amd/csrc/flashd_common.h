@@ -16,6 +16,8 @@ struct Problem {
     void* o;
     float* ws;          // split-K partial states, [splits][B][Hq][Lq][d + 2] fp32
     int B, Hq, Hkv, Lq, Lk, d;
+    int Li;             // causal rule: row r of a head stands for query position r % Li.  Li == Lq
+                        // except where the tile kernel runs the heads of a kv group as one head
     int dtype;          // flashd_dtype: 0 f32, 1 f16, 2 bf16
     int causal;         // 0/1
     int splits;         // >= 1

@@ -456,6 +456,7 @@ __device__ __forceinline__ void row_finish(float lam, float beta, float& fin, fl
 __device__ __forceinline__ int visible_count(const Problem& p, int i) {
     if (i >= p.Lq) return 0;
     if (!p.causal) return p.Lk;
+    if (p.Li != p.Lq) i %= p.Li;
     return min(max(i + p.shift + 1, 0), p.Lk);
 }
 

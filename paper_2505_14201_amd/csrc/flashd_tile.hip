@@ -331,6 +331,20 @@ struct Item {
     int jbase;                  // first key of tile 0
 };
 
+// Most and fewest keys visible to the rows r0 .. r1 (r0 <= r1 < Lq).  With the heads of a kv
+// group run as one head (Li < Lq) a range of rows may run over the end of a head; it then
+// holds that head's last position, which sees the most keys, and the next head's first.
+__device__ __forceinline__ void visible_range(const Problem& p, int r0, int r1, int& most,
+                                              int& fewest) {
+    if (p.Li != p.Lq && (r1 - r0 + 1 >= p.Li || r0 % p.Li > r1 % p.Li)) {
+        most = visible_count(p, p.Li - 1);
+        fewest = visible_count(p, 0);
+    } else {
+        most = visible_count(p, r1);
+        fewest = visible_count(p, r0);
+    }
+}
+
 // Item number seq of this workgroup, or an invalid item when the workgroup has run out of
 // work.  (A virtual workgroup that is a pair whose two row tiles coincide has one item; the
 // caller skips the other.)
@@ -377,9 +391,15 @@ __device__ __forceinline__ Item make_item(const Problem& p, const TileSched& sc,
     it.og = static_cast<uint16_t*>(p.o) + ((size_t)it.b * p.Hq + it.h) * (size_t)p.Lq * D;
     const int m0 = mt * kBM;
     it.wrow0 = m0 + wave * 32;
-    it.wmax = it.wrow0 < p.Lq ? visible_count(p, min(it.wrow0 + 31, p.Lq - 1)) : 0;
-    it.wmin = (it.wrow0 + 31 < p.Lq) ? visible_count(p, it.wrow0) : 0;
-    const int blk_nvis = visible_count(p, min(m0 + kBM - 1, p.Lq - 1));
+    it.wmax = 0;
+    it.wmin = 0;
+    if (it.wrow0 < p.Lq) {
+        int mn;
+        visible_range(p, it.wrow0, min(it.wrow0 + 31, p.Lq - 1), it.wmax, mn);
+        if (it.wrow0 + 31 < p.Lq) it.wmin = mn;      // a row past the end sees no key
+    }
+    int blk_nvis, blk_min;
+    visible_range(p, m0, min(m0 + kBM - 1, p.Lq - 1), blk_nvis, blk_min);
     const int tiles_all = (p.Lk + kBC - 1) / kBC;
     const int per_split = (tiles_all + p.splits - 1) / p.splits;
     const int t_begin = it.sp * per_split;
@@ -677,8 +697,10 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     const long units = (long)p.splits * p.B * p.Hq;
     TileSched sc;
     // Pairing halves the number of virtual workgroups; it pays once there are at least
-    // two rounds of them for all workgroup slots.
-    sc.pair = (p.causal && m_tiles >= 2 && m_tiles * units >= 2L * kXcds * slots_per_xcd) ? 1 : 0;
+    // two rounds of them for all workgroup slots.  (Not with the heads of a kv group run
+    // as one head: the row tiles of such a run do not grow in length from first to last.)
+    sc.pair = (p.causal && p.Li == p.Lq && m_tiles >= 2 &&
+               m_tiles * units >= 2L * kXcds * slots_per_xcd) ? 1 : 0;
     sc.wg_per_unit = (int)(sc.pair ? (m_tiles + 1) / 2 : m_tiles);
     sc.nx = units % kXcds == 0 ? kXcds : 1;
     const long nux = units / sc.nx;
@@ -692,8 +714,26 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     return sc;
 }
 
+// Grouped-query attention with few query positions per head: the g query heads of a kv head
+// read the same K and V, and in [B][Hq][Lq][d] their rows follow one another, so they can run
+// as one head of g * Lq rows (the causal rule then looks at the row index modulo Lq).  Taken
+// when that needs fewer row tiles than the heads one by one: 4 heads of 16 rows fill half a
+// row tile instead of an eighth of four, and K and V are streamed once for the group.
+static bool heads_as_one(int Hq, int Hkv, int Lq) {
+    constexpr long kBM = 32 * kNW;
+    const long g = Hq / Hkv;
+    if (g <= 1 || g * Lq > (1L << 30)) return false;
+    return (g * Lq + kBM - 1) / kBM < g * ((Lq + kBM - 1) / kBM);
+}
+
 template <typename T, int D>
-static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
+static hipError_t launch_tile_t(const Problem& p_in, bool online, hipStream_t st) {
+    Problem p = p_in;
+    if (heads_as_one(p.Hq, p.Hkv, p.Lq)) {
+        p.Li = p.Lq;
+        p.Lq *= p.Hq / p.Hkv;
+        p.Hq = p.Hkv;
+    }
     const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
     if (m_tiles * p.splits * p.B * p.Hq > 0x7fffffffL) return hipErrorInvalidValue;
     const int per_cu = online ? resident_per_cu<tile_kernel<T, D, true>>()
@@ -715,7 +755,11 @@ static hipError_t launch_tile_t(const Problem& p, bool online, hipStream_t st) {
 }
 
 long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d) {
-    (void)Hkv; (void)d;
+    (void)d;
+    if (heads_as_one(Hq, Hkv, Lq)) {
+        Lq *= Hq / Hkv;
+        Hq = Hkv;
+    }
     return (long)B * Hq * ((Lq + 32 * kNW - 1) / (32 * kNW));
 }
 

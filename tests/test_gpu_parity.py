@@ -355,3 +355,35 @@ def test_many_row_tiles_per_workgroup(shape, variant):
     idx = torch.from_numpy(rows.astype(np.int64))
     sel = got[idx[:, 0], idx[:, 1], idx[:, 2], :]
     check(sel, ref, DT[dtype], f"{shape} variant={variant}")
+
+
+# Grouped-query attention with few positions per head: the tile kernel runs the g query
+# heads of a kv head as one head of g * Lq rows (the causal rule then goes by the row index
+# modulo Lq).  Head boundaries inside a wavefront's 32 rows, inside a row tile and across
+# row tiles; more positions than keys (rows without keys in every head); key splits.
+#   (B, Hq, Hkv, Lq, Lk)
+PACKED_SHAPES = [
+    (2, 8, 2, 16, 500),       # 4 x 16 rows: half a row tile
+    (1, 8, 1, 40, 300),       # 320 rows in 3 row tiles instead of 8
+    (1, 6, 2, 130, 200),      # 390 rows, boundaries at 130 and 260
+    (2, 4, 2, 100, 260),
+    (1, 16, 2, 9, 1000),      # 72 rows: boundaries every 9 rows
+    (1, 8, 2, 50, 30),        # causal: the first 20 positions of every head see no key
+    (1, 12, 4, 33, 33),
+]
+
+
+@pytest.mark.parametrize("shape", PACKED_SHAPES)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant,dtype,d", [(TILE, "bf16", 128), (TILE, "f16", 64),
+                                             (ONLINE, "bf16", 64)])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_query_heads_of_a_kv_group_run_as_one_head(shape, causal, variant, dtype, d, splits):
+    B, Hq, Hkv, Lq, Lk = shape
+    w = synthetic.small("pack", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=8800 + Lq + Lk)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, w.scale)
+    got = run_flashd(q, k, v, causal, w.scale, variant, splits)
+    check(got, ref, DT[dtype], f"{shape} causal={causal} {dtype} d={d} v={variant} s={splits}")
+    if causal and Lq > Lk:
+        assert torch.count_nonzero(got[:, :, :Lq - Lk]) == 0, "rows without keys must be zeros"

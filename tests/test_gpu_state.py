@@ -138,3 +138,16 @@ def test_extreme_causal_shifts_show_every_key_or_none(shape, dtype):
         torch.cuda.synchronize()
         assert torch.count_nonzero(o) == 0, f"shift={shift}: rows without keys must be zeros"
         assert torch.isneginf(st[..., d] - st[..., d + 1]).all(), f"shift={shift}: empty state"
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_state_passing_with_query_heads_run_as_one_head(causal):
+    """Few positions per head and several query heads per kv head: the tile kernel packs the
+    group's heads into one run of rows; the state layout must not notice."""
+    B, Hq, Hkv, Lq, Lk, d = 2, 8, 2, 24, 400, 128
+    w = synthetic.small("state", B, Hq, Hkv, Lq, Lk, d, "bf16", causal, seed=940)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref_state = oa.attn_state(q, k, v, causal, w.scale)
+    o, st = run_chunks(q, k, v, causal, w.scale, (130, 257))
+    check(o, ref_state[..., :d], torch.bfloat16, f"packed state causal={causal} (o)")
+    check_state(st, ref_state, d, torch.bfloat16, f"packed state causal={causal}")
