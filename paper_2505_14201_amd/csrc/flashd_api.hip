@@ -43,8 +43,8 @@ int resolve_variant(const Shape& s, int variant) {
 
 int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
-// Splits for the automatic choice: enough independent work to fill 256 compute units
-// several times over, but never key ranges shorter than 256 keys.
+// Splits for the automatic choice: enough independent work to fill 256 compute units, but
+// never key ranges shorter than 256 keys.
 int auto_splits(const Shape& s, int variant) {
     long units;
     if (variant == FLASHD_VARIANT_PER_KEY) {
@@ -55,12 +55,12 @@ int auto_splits(const Shape& s, int variant) {
     } else {
         units = flashd::tile_workgroups(s.B, s.Hq, s.Hkv, s.Lq, s.d);
     }
-    // Two workgroups are resident per compute unit (512 in all).  The decode kernel
-    // streams at the same rate with one full round of them as with several, so it is not
-    // split further once a round is full; the other kernels want two rounds for balance.
-    const bool decode = variant != FLASHD_VARIANT_PER_KEY &&
-                        flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
-    const long target = decode ? 512 : 1024;
+    // Two workgroups are resident per compute unit (512 in all), and one full round of them
+    // is what the matrix-core kernels want: measured over decode, short-query and prefill
+    // shapes of 64 to 512 units, the fastest split count is the one that brings the launch
+    // to 256-512 workgroups; more of them only add partial states to write and merge.  The
+    // per-key kernel keeps two rounds.
+    const long target = variant == FLASHD_VARIANT_PER_KEY ? 1024 : 512;
     if (units < 1) units = 1;
     long sp = units >= target ? 1 : ceil_div(target, units);
     const long by_len = s.Lk / 256 > 0 ? s.Lk / 256 : 1;
