@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true", help="skip the decode side measurement")
     ap.add_argument("--no-ablation", action="store_true")
     ap.add_argument("--no-kv8", action="store_true", help="skip the fp8 K/V decode measurement")
+    ap.add_argument("--no-decode16", action="store_true",
+                    help="skip the decode measurement with 16 query positions per head")
     ap.add_argument("--no-state", action="store_true",
                     help="skip the two-chunk run through flashd_attn_fwd_state")
     ap.add_argument("--no-skip-stats", action="store_true",
@@ -270,25 +272,26 @@ def main() -> int:
                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
                                       "traffic": TRAFFIC_DECODE_BYTES}}
-        # the same KV cache read for 16 query positions per head at once (speculative decoding,
-        # a short chunk): (Hq / Hkv) * Lq = 64 rows per kv head, past the decode kernel's 32, so
-        # the tile kernel runs it with the heads of a kv group as one head, key range split
-        gen = torch.Generator().manual_seed(wd.seed + 16)
-        q16 = torch.randn((wd.B, wd.Hq, 16, wd.d), generator=gen).to(qg.dtype).cuda()
-        o16 = torch.empty_like(q16)
+        if not args.no_decode16:
+            # the same KV cache read for 16 query positions per head at once (speculative decoding,
+            # a short chunk): (Hq / Hkv) * Lq = 64 rows per kv head, past the decode kernel's 32, so
+            # the tile kernel runs it with the heads of a kv group as one head, key range split
+            gen = torch.Generator().manual_seed(wd.seed + 16)
+            q16 = torch.randn((wd.B, wd.Hq, 16, wd.d), generator=gen).to(qg.dtype).cuda()
+            o16 = torch.empty_like(q16)
 
-        def step_16(_):
-            flashd.attn_fwd(q16, kg, vg, o16, True, wd.scale)
-        _, ev16 = time_calls(step_16, dsteps, 5, 1)
-        ms16 = ev16 / dsteps
-        bytes16 = (kg.numel() + vg.numel() + 2 * q16.numel()) * kg.element_size()
-        gbs16 = bytes16 / (ms16 * 1e-3) / 1e9
-        out["decode_16_positions"] = {"ms_per_step": round(ms16, 4), "bytes_per_step": bytes16,
-                                      "roofline": {"bound": "hbm", "achieved": round(gbs16, 1),
-                                                   "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                                   "frac": round(gbs16 / PEAK_HBM_GBS, 4),
-                                                   "traffic": None}}
-        del q16, o16
+            def step_16(_):
+                flashd.attn_fwd(q16, kg, vg, o16, True, wd.scale)
+            _, ev16 = time_calls(step_16, dsteps, 5, 1)
+            ms16 = ev16 / dsteps
+            bytes16 = (kg.numel() + vg.numel() + 2 * q16.numel()) * kg.element_size()
+            gbs16 = bytes16 / (ms16 * 1e-3) / 1e9
+            out["decode_16_positions"] = {"ms_per_step": round(ms16, 4), "bytes_per_step": bytes16,
+                                          "roofline": {"bound": "hbm", "achieved": round(gbs16, 1),
+                                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                       "frac": round(gbs16 / PEAK_HBM_GBS, 4),
+                                                       "traffic": None}}
+            del q16, o16
         if not args.no_kv8:
             # the same decode workload with K and V stored as fp8 (flashd_attn_fwd_kv8)
             ks_, vs_ = 2.0 ** -5, 2.0 ** -5

@@ -201,7 +201,7 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.q = q; p.k = k; p.v = v; p.o = o;
     p.ws = static_cast<float*>(ws);
     p.B = s.B; p.Hq = s.Hq; p.Hkv = s.Hkv; p.Lq = s.Lq; p.Lk = s.Lk; p.d = s.d;
-    p.Li = s.Lq;
+    p.Li = flashd::make_fast_div((uint32_t)s.Lq);
     p.dtype = s.dtype;
     p.causal = causal != 0;
     p.splits = sp;
@@ -294,7 +294,7 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     Problem p;
     p.q = q; p.k = k; p.v = nullptr; p.o = nullptr; p.ws = nullptr;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Lq = Lq; p.Lk = Lk; p.d = d;
-    p.Li = Lq;
+    p.Li = flashd::make_fast_div((uint32_t)Lq);
     p.dtype = dtype;
     p.causal = causal != 0;
     p.splits = 1;

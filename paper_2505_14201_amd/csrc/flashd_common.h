@@ -9,6 +9,31 @@ namespace flashd {
 
 constexpr int kWave = 64;
 
+// Division of a 32-bit unsigned number by a divisor fixed at launch, without a division
+// instruction (Granlund and Montgomery's round-up multiplier: with l = ceil(log2 d) and
+// m = floor(2^32 (2^l - d) / d) + 1, the quotient of any n < 2^32 is
+// (t + ((n - t) >> min(l, 1))) >> max(l - 1, 0), t = high word of m * n; exact for d >= 1).
+struct FastDiv {
+    uint32_t d, m;
+    int s1, s2;
+};
+
+inline FastDiv make_fast_div(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    int l = 0;
+    while ((1ull << l) < (unsigned long long)d) ++l;
+    f.m = (uint32_t)((((1ull << l) - (unsigned long long)d) << 32) / (unsigned long long)d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 1 ? l - 1 : 0;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
 struct Problem {
     const void* q;
     const void* k;
@@ -16,8 +41,6 @@ struct Problem {
     void* o;
     float* ws;          // split-K partial states, [splits][B][Hq][Lq][d + 2] fp32
     int B, Hq, Hkv, Lq, Lk, d;
-    int Li;             // causal rule: row r of a head stands for query position r % Li.  Li == Lq
-                        // except where the tile kernel runs the heads of a kv group as one head
     int dtype;          // flashd_dtype: 0 f32, 1 f16, 2 bf16
     int causal;         // 0/1
     int splits;         // >= 1
@@ -32,6 +55,8 @@ struct Problem {
     float oscale;       // factor on the output (and on the o of partial states); 1 unless kv8
     const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32
     float* state_out;        // optional state after this call's keys, same layout
+    FastDiv Li;         // causal rule: row r of a head stands for query position r % Li.d.  Li.d == Lq
+                        // except where the tile kernel runs the heads of a kv group as one head
 };
 
 // ---- storage types -------------------------------------------------------

@@ -453,11 +453,18 @@ __device__ __forceinline__ void row_finish(float lam, float beta, float& fin, fl
     }
 }
 
+// Keys visible to query position pos of a head (0 <= pos < Li.d).
+__device__ __forceinline__ int visible_at(const Problem& p, int pos) {
+    if (!p.causal) return p.Lk;
+    return min(max(pos + p.shift + 1, 0), p.Lk);
+}
+
+// Keys visible to row i of a head as the kernel sees heads (Lq rows, row i standing for
+// position i % Li.d); rows past the end see none.
 __device__ __forceinline__ int visible_count(const Problem& p, int i) {
     if (i >= p.Lq) return 0;
-    if (!p.causal) return p.Lk;
-    if (p.Li != p.Lq) i %= p.Li;
-    return min(max(i + p.shift + 1, 0), p.Lk);
+    // i % Li, branch-free: the rule runs per lane
+    return visible_at(p, i - (int)(fast_div((uint32_t)i, p.Li) * p.Li.d));
 }
 
 }  // namespace flashd

@@ -312,15 +312,23 @@ __device__ __forceinline__ void phase_output(const uint16_t* vs, TileRegs<D>& g,
 struct TileSched {
     int pair;          // 1: a virtual workgroup is row tiles (m_tiles - 1 - r) and r of its unit
     int wg_per_unit;   // virtual workgroups per (split, b, h) unit
-    int nx;            // 8: unit u runs on XCD u % 8 (ids go round-robin over the XCDs); 1: no such mapping
+    int nx_log2;       // 3: unit u runs on XCD u % 8 (ids go round-robin over the XCDs); 0: no such mapping
     int group;         // units of one XCD that are in flight together
     int total;         // virtual workgroups
+    // fixed per launch, so that a workgroup finds its work without a division instruction
+    int nux;           // units per XCD
+    int per_split;     // key tiles per split
+    FastDiv gw;        // virtual workgroups of a full group: group * wg_per_unit
+    FastDiv gfull;     // units in a full group: group
+    FastDiv glast;     // units in the last group of an XCD: nux % group (or group)
+    FastDiv n_bh;      // units per split: B * Hq
+    FastDiv g;         // query heads per kv head
 };
 
 // One row tile of one unit as seen by a wavefront.  All members are wavefront-uniform.
 struct Item {
     bool valid;
-    int sp, b, h;               // split, batch, query head
+    int sp, bh, unit;           // split, b * Hq + h, sp * B * Hq + bh
     const uint16_t* qg;         // this head's Q, K, V, O
     const uint16_t* kg;
     const uint16_t* vg;
@@ -331,18 +339,15 @@ struct Item {
     int jbase;                  // first key of tile 0
 };
 
-// Most and fewest keys visible to the rows r0 .. r1 (r0 <= r1 < Lq).  With the heads of a kv
-// group run as one head (Li < Lq) a range of rows may run over the end of a head; it then
-// holds that head's last position, which sees the most keys, and the next head's first.
+// Most and fewest keys visible to the rows r0 .. r1 (r0 <= r1 < Lq), or bounds of them.  With
+// the heads of a kv group run as one head (Li.d < Lq) a range of rows may run over the end of a
+// head; the bounds are then those of a whole head, its last and its first position (they only
+// decide which tiles a wavefront may skip and which take the code path without the mask).
 __device__ __forceinline__ void visible_range(const Problem& p, int r0, int r1, int& most,
                                               int& fewest) {
-    if (p.Li != p.Lq && (r1 - r0 + 1 >= p.Li || r0 % p.Li > r1 % p.Li)) {
-        most = visible_count(p, p.Li - 1);
-        fewest = visible_count(p, 0);
-    } else {
-        most = visible_count(p, r1);
-        fewest = visible_count(p, r0);
-    }
+    const bool whole_head = (int)p.Li.d != p.Lq;
+    most = visible_at(p, whole_head ? (int)p.Li.d - 1 : r1);
+    fewest = visible_at(p, whole_head ? 0 : r0);
 }
 
 // Item number seq of this workgroup, or an invalid item when the workgroup has run out of
@@ -356,39 +361,36 @@ __device__ __forceinline__ Item make_item(const Problem& p, const TileSched& sc,
     it.valid = false;
     it.n = 0;
     skip = false;
-    const int ipv = sc.pair ? 2 : 1;
-    const int v = blockIdx.x + (seq / ipv) * gridDim.x;
+    const int v = blockIdx.x + (seq >> sc.pair) * gridDim.x;
     if (v >= sc.total) return it;
     // virtual workgroup id -> (unit, rank of the row tile within the unit)
     const int m_tiles = (p.Lq + kBM - 1) / kBM;
-    const int n_bh = p.B * p.Hq;
-    const int xcd = v % sc.nx;
-    const int local = v / sc.nx;
-    const int nux = (n_bh * p.splits) / sc.nx;         // units on this XCD
-    const int gw = sc.group * sc.wg_per_unit;
-    const int grp = local / gw;
-    const int within = local % gw;
-    const int gsz = min(sc.group, nux - grp * sc.group);
-    const int rank = within / gsz;                      // slowest inside a group
-    const int unit = xcd + sc.nx * (grp * sc.group + within % gsz);
+    const int xcd = v & ((1 << sc.nx_log2) - 1);
+    const int local = v >> sc.nx_log2;
+    const int grp = (int)fast_div((uint32_t)local, sc.gw);
+    const int within = local - grp * (int)sc.gw.d;
+    const bool last = (grp + 1) * sc.group > sc.nux;             // the XCD's last, shorter group
+    const int gsz = last ? (int)sc.glast.d : sc.group;
+    const int rank = (int)(last ? fast_div((uint32_t)within, sc.glast)
+                                : fast_div((uint32_t)within, sc.gfull));     // slowest inside a group
+    const int unit = xcd + ((grp * sc.group + within - rank * gsz) << sc.nx_log2);
     int mt;
     if (sc.pair) {
         // the longer row tile first
-        mt = (seq % ipv) == 0 ? m_tiles - 1 - rank : rank;
-        if ((seq % ipv) == 1 && m_tiles - 1 - rank == rank) { skip = true; return it; }
+        mt = (seq & 1) == 0 ? m_tiles - 1 - rank : rank;
+        if ((seq & 1) == 1 && m_tiles - 1 - rank == rank) { skip = true; return it; }
     } else {
         mt = p.causal ? m_tiles - 1 - rank : rank;
     }
     it.valid = true;
-    it.sp = unit / n_bh;
-    const int bh = unit % n_bh;
-    it.b = bh / p.Hq;
-    it.h = bh % p.Hq;
-    const int kvh = it.h / (p.Hq / p.Hkv);
-    it.qg = static_cast<const uint16_t*>(p.q) + ((size_t)it.b * p.Hq + it.h) * (size_t)p.Lq * D;
-    it.kg = static_cast<const uint16_t*>(p.k) + ((size_t)it.b * p.Hkv + kvh) * (size_t)p.Lk * D;
-    it.vg = static_cast<const uint16_t*>(p.v) + ((size_t)it.b * p.Hkv + kvh) * (size_t)p.Lk * D;
-    it.og = static_cast<uint16_t*>(p.o) + ((size_t)it.b * p.Hq + it.h) * (size_t)p.Lq * D;
+    it.unit = unit;
+    it.sp = (int)fast_div((uint32_t)unit, sc.n_bh);
+    it.bh = unit - it.sp * (int)sc.n_bh.d;
+    const size_t kv_unit = fast_div((uint32_t)it.bh, sc.g);     // b * Hkv + h / g
+    it.qg = static_cast<const uint16_t*>(p.q) + (size_t)it.bh * (size_t)p.Lq * D;
+    it.kg = static_cast<const uint16_t*>(p.k) + kv_unit * (size_t)p.Lk * D;
+    it.vg = static_cast<const uint16_t*>(p.v) + kv_unit * (size_t)p.Lk * D;
+    it.og = static_cast<uint16_t*>(p.o) + (size_t)it.bh * (size_t)p.Lq * D;
     const int m0 = mt * kBM;
     it.wrow0 = m0 + wave * 32;
     it.wmax = 0;
@@ -400,10 +402,8 @@ __device__ __forceinline__ Item make_item(const Problem& p, const TileSched& sc,
     }
     int blk_nvis, blk_min;
     visible_range(p, m0, min(m0 + kBM - 1, p.Lq - 1), blk_nvis, blk_min);
-    const int tiles_all = (p.Lk + kBC - 1) / kBC;
-    const int per_split = (tiles_all + p.splits - 1) / p.splits;
-    const int t_begin = it.sp * per_split;
-    const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + per_split);
+    const int t_begin = it.sp * sc.per_split;
+    const int t_end = min((blk_nvis + kBC - 1) / kBC, t_begin + sc.per_split);
     it.n = max(t_end - t_begin, 0);
     it.jbase = t_begin * kBC;
     return it;
@@ -518,7 +518,7 @@ void tile_kernel(Problem p, TileSched sc) {
             // continue from the state of earlier keys: o = U with beta = 1, R = Lam
             const int row = min(cur.wrow0 + col, p.Lq - 1);
             const float* src = p.state_in +
-                               (((size_t)cur.b * p.Hq + cur.h) * (size_t)p.Lq + row) * (D + 2);
+                               ((size_t)cur.bh * (size_t)p.Lq + row) * (D + 2);
             const float lam_in = src[D] - src[D + 1];            // s - ln w, natural log
             if (cur.wrow0 + col < p.Lq && lam_in != ninf) {
 #pragma unroll
@@ -655,9 +655,7 @@ void tile_kernel(Problem p, TileSched sc) {
         }
         if (p.partial && cur.wrow0 + col < p.Lq) {
             // partial state (o, s, ln w) in natural-log units: the run is one key of score Lam
-            float* dst = p.ws + ((((size_t)cur.sp * p.B + cur.b) * p.Hq + cur.h) * (size_t)p.Lq +
-                                 cur.wrow0 + col) *
-                                    (D + 2);
+            float* dst = p.ws + ((size_t)cur.unit * (size_t)p.Lq + cur.wrow0 + col) * (D + 2);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -699,11 +697,12 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     // Pairing halves the number of virtual workgroups; it pays once there are at least
     // two rounds of them for all workgroup slots.  (Not with the heads of a kv group run
     // as one head: the row tiles of such a run do not grow in length from first to last.)
-    sc.pair = (p.causal && p.Li == p.Lq && m_tiles >= 2 &&
+    sc.pair = (p.causal && (int)p.Li.d == p.Lq && m_tiles >= 2 &&
                m_tiles * units >= 2L * kXcds * slots_per_xcd) ? 1 : 0;
     sc.wg_per_unit = (int)(sc.pair ? (m_tiles + 1) / 2 : m_tiles);
-    sc.nx = units % kXcds == 0 ? kXcds : 1;
-    const long nux = units / sc.nx;
+    sc.nx_log2 = units % kXcds == 0 ? 3 : 0;
+    static_assert(kXcds == 8, "the unit -> XCD mapping shifts by 3");
+    const long nux = units >> sc.nx_log2;
     // Virtual workgroups that all carry the same work (paired, or no mask): run as few
     // units at a time as fill the XCD, so that their K/V stay in its L2.  Unpaired causal
     // tiles differ in length: all units together, longest tiles first.
@@ -711,6 +710,14 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     if (sc.pair || !p.causal) group = std::max(1L, (long)slots_per_xcd / sc.wg_per_unit);
     sc.group = (int)std::min(group, nux);
     sc.total = (int)(sc.wg_per_unit * units);
+    sc.nux = (int)nux;
+    const long tiles_all = (p.Lk + kBC - 1) / kBC;
+    sc.per_split = (int)((tiles_all + p.splits - 1) / p.splits);
+    sc.gw = make_fast_div((uint32_t)(sc.group * sc.wg_per_unit));
+    sc.gfull = make_fast_div((uint32_t)sc.group);
+    sc.glast = make_fast_div((uint32_t)(nux % sc.group != 0 ? nux % sc.group : sc.group));
+    sc.n_bh = make_fast_div((uint32_t)(p.B * p.Hq));
+    sc.g = make_fast_div((uint32_t)(p.Hq / p.Hkv));
     return sc;
 }
 
@@ -730,7 +737,7 @@ template <typename T, int D>
 static hipError_t launch_tile_t(const Problem& p_in, bool online, hipStream_t st) {
     Problem p = p_in;
     if (heads_as_one(p.Hq, p.Hkv, p.Lq)) {
-        p.Li = p.Lq;
+        p.Li = make_fast_div((uint32_t)p.Lq);
         p.Lq *= p.Hq / p.Hkv;
         p.Hq = p.Hkv;
     }
