@@ -153,74 +153,111 @@ void perkey_kernel(Problem p) {
     }
 }
 
-// Fold the split partials of each query row left to right with the sigmoid rule, after the
-// state of earlier keys if one is given (p.state_in).  Writes the output (p.o, if not null)
-// and the state (p.state_out, if not null) as the run seen as one key: (o, s = Lam, ln w = 0).
-// state_out may be the buffer the single partial came from (same row, read before written).
-template <typename T, int D>
+// Fold the split partials of each query row with the sigmoid rule, together with the state of
+// earlier keys if one is given (p.state_in).  Writes the output (p.o, if not null) and the
+// state (p.state_out, if not null) as the run seen as one key: (o, s = Lam, ln w = 0).
+//
+// One wavefront per row.  Folded one after the other, o <- o + (o_p - o) W_p with
+// W_p = sigmoid(Lam_p - Lam) and Lam <- Lam_p - ln W_p, the partials end up with the weights
+// e^{Lam_p - Lam_total} (the product of a partial's own W_p and the 1 - W of every later
+// step), and the fold of the Lam alone does not need the o.  So: each lane takes the Lam of
+// one partial (at most 64 splits), a butterfly of sigmoid merges gives every lane Lam_total
+// (the rule is associative and commutative; no maximum is taken, and Lam_total >= Lam_p keeps
+// every exponent at or below zero), and the output is one pass of independent loads,
+// sum_p e^{Lam_p - Lam_total} o_p.  Left to right instead, a launch with 64 splits and few
+// rows waits for memory 64 times in a row (43 us, against 22 us for the kernel that wrote
+// the partials; a few us this way).
+// state_out may be the buffer the single partial came from, or state_in: a wavefront reads
+// all of its row before it writes.
+template <typename T, int D, int kBatch>            // kBatch: partial rows in flight per lane
 __global__ __launch_bounds__(256)
 void merge_splits_kernel(Problem p) {
-    constexpr int C = D / 4;                       // threads per row, 4 elements each
+    constexpr int E = D / kWave;                   // output elements per lane
+    const float ninf = -__builtin_inff();
     const size_t rows = (size_t)p.B * p.Hq * p.Lq;
-    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t row = gid / C;
-    const int c = (int)(gid % C);
-    if (row >= rows) return;
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    float lam = -__builtin_inff();
-    if (p.state_in) {
-        const float* src = p.state_in + row * (D + 2);
-        lam = src[D] - src[D + 1];
-        if (lam != -__builtin_inff()) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t row = (size_t)blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
+    if (row >= rows) return;                       // the whole wavefront leaves together
+
+    // the first batch of partial rows is requested before the weights are known: the loads
+    // do not depend on them, and the fold of the Lam then runs while they are in flight
+    float ob[kBatch][E];
+    auto fetch = [&](int sp0) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) acc[t] = src[c * 4 + t];
-        }
-    }
-    // The partials are folded left to right, but fetched kChunk at a time: the loads do not
-    // depend on the fold, and one memory round trip per partial would make a launch with
-    // many splits and few rows wait 64 times in a row (43 us for 64 splits, against 22 us
-    // for the kernel that wrote them).
-    constexpr int kChunk = 16;
-    for (int sp0 = 0; sp0 < p.splits; sp0 += kChunk) {
-        float lam_b[kChunk], ob[kChunk][4];
-#pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
+        for (int u = 0; u < kBatch; ++u) {
             const int sp = min(sp0 + u, p.splits - 1);
             const float* src = p.ws + ((size_t)sp * rows + row) * (D + 2);
-            lam_b[u] = src[D] - src[D + 1];        // s - ln w
 #pragma unroll
-            for (int t = 0; t < 4; ++t) ob[u][t] = src[c * 4 + t];
+            for (int e = 0; e < E; ++e) ob[u][e] = src[lane * E + e];
         }
+    };
+    fetch(0);
+    float lam_p = ninf;
+    if (lane < p.splits) {
+        const float* src = p.ws + ((size_t)lane * rows + row) * (D + 2);
+        lam_p = src[D] - src[D + 1];               // s - ln w
+    }
+    float lam_in = ninf;
+    float oin[E];
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            if (sp0 + u < p.splits) {
-                float W, lam_n;
-                merge_weight(lam, lam_b[u], W, lam_n);
-                lam = lam_n;
-                if (W != 0.0f) {
+    for (int e = 0; e < E; ++e) oin[e] = 0.0f;
+    if (p.state_in) {
+        const float* sin = p.state_in + row * (D + 2);
+        lam_in = sin[D] - sin[D + 1];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) acc[t] = fmaf(ob[u][t] - acc[t], W, acc[t]);
-                }
+        for (int e = 0; e < E; ++e) oin[e] = sin[lane * E + e];
+    }
+    float tot = lam_p;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const float other = __shfl_xor(tot, off);
+        const bool upper = (lane & off) != 0;      // both lanes of a pair fold (lower, upper)
+        float W;
+        merge_weight(upper ? other : tot, upper ? tot : other, W, tot);
+    }
+    {
+        float W;
+        merge_weight(lam_in, tot, W, tot);
+    }
+    const float w_p = lam_p == ninf ? 0.0f : __expf(lam_p - tot);
+    const float w_in = lam_in == ninf ? 0.0f : __expf(lam_in - tot);
+
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = w_in != 0.0f ? w_in * oin[e] : 0.0f;
+    for (int sp0 = 0; sp0 < p.splits; sp0 += kBatch) {
+        if (sp0 > 0) fetch(sp0);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const float w = sp0 + u < p.splits ? __shfl(w_p, sp0 + u) : 0.0f;
+            if (w != 0.0f) {                       // a partial of weight 0 may hold anything
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] = fmaf(w, ob[u][e], acc[e]);
             }
         }
     }
     if (p.o) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) Store<T>::store(p.o, row * D + c * 4 + t, acc[t]);
+        for (int e = 0; e < E; ++e) Store<T>::store(p.o, row * D + lane * E + e, acc[e]);
     }
     if (p.state_out) {
         float* dst = p.state_out + row * (D + 2);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) dst[c * 4 + t] = acc[t];
-        if (c == 0) { dst[D] = lam; dst[D + 1] = 0.0f; }
+        for (int e = 0; e < E; ++e) dst[lane * E + e] = acc[e];
+        if (lane == 0) { dst[D] = tot; dst[D + 1] = 0.0f; }
     }
 }
 
 template <typename T, int D>
 static hipError_t launch_merge_t(const Problem& p, hipStream_t st) {
-    const size_t threads = (size_t)p.B * p.Hq * p.Lq * (D / 4);
-    const unsigned blocks = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL((merge_splits_kernel<T, D>), dim3(blocks), dim3(256), 0, st, p);
+    const size_t rows = (size_t)p.B * p.Hq * p.Lq;
+    if ((rows + 3) / 4 > 0x7fffffffull) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((rows + 3) / 4);
+    // many splits come with few rows: more loads in flight per lane, fewer round trips
+    if (p.splits > 8)
+        hipLaunchKernelGGL((merge_splits_kernel<T, D, 32>), dim3(blocks), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((merge_splits_kernel<T, D, 8>), dim3(blocks), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
