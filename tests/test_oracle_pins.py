@@ -318,6 +318,29 @@ def test_merge_is_associative_commutative_with_identity():
         assert np.array_equal(x[0], a[0]) and x[1] == a[1]
 
 
+def test_runs_merged_one_after_the_other_end_with_softmax_weights_over_their_lambdas():
+    """Sec. III-A's closed form w_i = e^{s_i} / sum_{j<=i} e^{s_j} applied to runs as keys:
+    after all merges run p carries the weight e^{Lam_p - Lam_total}, Lam_total the fold of
+    the Lam alone -- so the merged output is sum_p e^{Lam_p - Lam_total} o_p."""
+    rng = np.random.default_rng(21)
+    runs = []
+    for n in (4, 1, 9, 0, 6, 2):
+        runs.append(rec.state_of_run(rng.standard_normal(n) * 7, rng.standard_normal((n, 5))))
+    st = (np.zeros(5), rec.EMPTY_LAMBDA)
+    lam_only = (np.zeros(5), rec.EMPTY_LAMBDA)
+    for r in runs:
+        st = rec.merge(st, r)
+        lam_only = rec.merge(lam_only, (np.zeros(5), r[1]))
+    assert abs(st[1] - lam_only[1]) < 1e-13
+    lams = np.array([r[1] for r in runs])
+    np.testing.assert_allclose(st[1], scipy.special.logsumexp(lams[np.isfinite(lams)]),
+                               rtol=0, atol=1e-12)
+    weights = np.where(np.isfinite(lams), np.exp(lams - st[1]), 0.0)
+    np.testing.assert_allclose(weights.sum(), 1.0, rtol=0, atol=1e-13)
+    direct = sum(w * r[0] for w, r in zip(weights, runs))
+    np.testing.assert_allclose(direct, st[0], rtol=0, atol=1e-13)
+
+
 @pytest.mark.parametrize("algo", ALGOS)
 def test_key_permutation_invariance(algo):
     rng = np.random.default_rng(16)
