@@ -63,7 +63,15 @@ int auto_splits(const Shape& s, int variant) {
     const long target = variant == FLASHD_VARIANT_PER_KEY ? 1024 : 512;
     if (units < 1) units = 1;
     long sp = units >= target ? 1 : ceil_div(target, units);
-    const long by_len = s.Lk / 256 > 0 ? s.Lk / 256 : 1;
+    // A split costs its partial states: (d + 2) floats per query row written and read back.
+    // With one row per head (decode) that is nothing and 256 keys are enough to pay for a
+    // split; the tile kernel's workgroups carry 128 rows each, and measured over prefill
+    // shapes a split only pays once it still holds some 2048 keys (B1 H32 L1024 causal:
+    // 23 us unsplit, 39 us in two splits of 512 keys).
+    const bool tile = variant != FLASHD_VARIANT_PER_KEY &&
+                      !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
+    const long min_keys = tile ? 2048 : 256;
+    const long by_len = s.Lk / min_keys > 0 ? s.Lk / min_keys : 1;
     if (sp > by_len) sp = by_len;
     if (sp > FLASHD_MAX_SPLITS) sp = FLASHD_MAX_SPLITS;
     if (sp < 1) sp = 1;

@@ -696,8 +696,10 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     TileSched sc;
     // Pairing halves the number of virtual workgroups; it pays once there are at least
     // two rounds of them for all workgroup slots.  (Not with the heads of a kv group run
-    // as one head: the row tiles of such a run do not grow in length from first to last.)
-    sc.pair = (p.causal && (int)p.Li.d == p.Lq && m_tiles >= 2 &&
+    // as one head: the row tiles of such a run do not grow in length from first to last.  Not
+    // with split keys either: a split's share of a long and of a short row tile do not add up
+    // to the same for every pair.)
+    sc.pair = (p.causal && p.splits == 1 && (int)p.Li.d == p.Lq && m_tiles >= 2 &&
                m_tiles * units >= 2L * kXcds * slots_per_xcd) ? 1 : 0;
     sc.wg_per_unit = (int)(sc.pair ? (m_tiles + 1) / 2 : m_tiles);
     sc.nx_log2 = units % kXcds == 0 ? 3 : 0;
