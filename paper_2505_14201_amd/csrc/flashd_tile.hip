@@ -101,10 +101,12 @@ __device__ __forceinline__ void wait_copies() {
 // Start the copy of the K and V tiles whose first key is j0 into ks / vs (the wavefront
 // fills its own 16 rows of each).  A tile that sticks out past the last key takes the slow
 // form with rows clamped to the last key (masked later).
-template <int D>
+template <int D, bool NT = false>
 __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg, int j0, int Lk,
                                           const DmaLane<D>& dl, int wave, int lane,
                                           uint16_t* ks, uint16_t* vs) {
+    // NT: the non-temporal cache policy, for K and V that no other workgroup will read
+    constexpr int kAux = NT ? 2 : 0;
     using C = TileCfg<D>;
     constexpr int NI = DmaLane<D>::NI;
     uint16_t* kw = ks + wave * (NI * 512);
@@ -121,13 +123,13 @@ __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg
             constexpr int N = decltype(n)::value;
             uint32_t off = dl.koff[N];
             asm volatile("" : "+v"(off));
-            __builtin_amdgcn_global_load_lds((gptr_t)(kt + off), (lptr_t)kw, 16, 1024 * N, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(kt + off), (lptr_t)kw, 16, 1024 * N, kAux);
         };
         uint32_t voff = dl.voff;
         asm volatile("" : "+v"(voff));
         auto issue_v = [&](auto n) {
             constexpr int N = decltype(n)::value;
-            __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff), (lptr_t)vw, 16, 1024 * N, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(vt + voff), (lptr_t)vw, 16, 1024 * N, kAux);
         };
         issue(IntC<0>{}); issue(IntC<1>{});
         if constexpr (NI == 4) { issue(IntC<2>{}); issue(IntC<3>{}); }
@@ -142,9 +144,9 @@ __device__ __forceinline__ void tile_copy(const uint16_t* kg, const uint16_t* vg
             const int cs = slot % C::CPR;
             const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
             __builtin_amdgcn_global_load_lds((gptr_t)(kg + grow + 8 * (cs ^ C::swz_k(row))),
-                                             (lptr_t)(kw + n * 512), 16, 0, 0);
+                                             (lptr_t)(kw + n * 512), 16, 0, kAux);
             __builtin_amdgcn_global_load_lds((gptr_t)(vg + grow + 8 * (cs ^ C::swz_v(row))),
-                                             (lptr_t)(vw + n * 512), 16, 0, 0);
+                                             (lptr_t)(vw + n * 512), 16, 0, kAux);
         }
     }
 }
@@ -315,6 +317,7 @@ struct TileSched {
     int nx_log2;       // 3: unit u runs on XCD u % 8 (ids go round-robin over the XCDs); 0: no such mapping
     int group;         // units of one XCD that are in flight together
     int total;         // virtual workgroups
+    int once;          // 1: no two workgroups read the same K and V (one row tile per kv head)
     // fixed per launch, so that a workgroup finds its work without a division instruction
     int nux;           // units per XCD
     int per_split;     // key tiles per split
@@ -558,7 +561,12 @@ void tile_kernel(Problem p, TileSched sc) {
             const int j0 = cur.jbase + t * kBC;
             uint16_t* kdst = lds + (PAR ^ 1) * kTile;
             if (t + 1 < cur.n) {
-                tile_copy<D>(cur.kg, cur.vg, j0 + kBC, p.Lk, dl, wave, lane, kdst, kdst + 2 * kTile);
+                if (sc.once)
+                    tile_copy<D, true>(cur.kg, cur.vg, j0 + kBC, p.Lk, dl, wave, lane, kdst,
+                                       kdst + 2 * kTile);
+                else
+                    tile_copy<D>(cur.kg, cur.vg, j0 + kBC, p.Lk, dl, wave, lane, kdst,
+                                 kdst + 2 * kTile);
             } else if (PAR == 1 && nxt.n > 0) {
                 tile_copy<D>(nxt.kg, nxt.vg, nxt.jbase, p.Lk, dl, wave, lane, kdst,
                              kdst + 2 * kTile);
@@ -712,6 +720,7 @@ static TileSched tile_sched(const Problem& p, int slots_per_xcd) {
     if (sc.pair || !p.causal) group = std::max(1L, (long)slots_per_xcd / sc.wg_per_unit);
     sc.group = (int)std::min(group, nux);
     sc.total = (int)(sc.wg_per_unit * units);
+    sc.once = (m_tiles == 1 && p.Hq == p.Hkv) ? 1 : 0;
     sc.nux = (int)nux;
     const long tiles_all = (p.Lk + kBC - 1) / kBC;
     sc.per_split = (int)((tiles_all + p.splits - 1) / p.splits);
