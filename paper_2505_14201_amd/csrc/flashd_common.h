@@ -29,8 +29,8 @@ inline FastDiv make_fast_div(uint32_t d) {
     return f;
 }
 
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
-    const uint32_t t = __umulhi(f.m, n);
+__host__ __device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
+    const uint32_t t = (uint32_t)(((uint64_t)f.m * n) >> 32);       // one v_mul_hi_u32
     return (t + ((n - t) >> f.s1)) >> f.s2;
 }
 
