@@ -211,6 +211,20 @@ def main() -> int:
             "kernel_ms": round(ev_abl / args.steps, 4),
             "TFLOP/s": round(flops / (ev_abl / args.steps * 1e-3) / 1e12, 2)}
 
+    if not args.no_ablation:
+        # Alg. 3 literally, one sigmoid per key on the vector ALUs (variant PER_KEY): what
+        # lifting the recurrence to key tiles on the matrix cores buys
+        pk_steps = 5
+
+        def step_pk(i):
+            qg, kg, vg, og = sets[i]
+            flashd.attn_fwd_ex(qg, kg, vg, og, w.causal, w.scale, flashd.VARIANT_PER_KEY, 1)
+        step_pk(0)
+        _, ev_pk = time_calls(step_pk, pk_steps, 0, args.sets)
+        out["per_key_literal"] = {
+            "kernel_ms": round(ev_pk / pk_steps, 3),
+            "TFLOP/s": round(flops / (ev_pk / pk_steps * 1e-3) / 1e12, 2)}
+
     if not args.no_skip_stats:
         # Sec. III-C / Table I on synthetic inputs: share of Alg. 3 steps whose score
         # difference leaves the static range [-6, 11]
