@@ -3,7 +3,8 @@
 // inputs use it) and the slow reference for the tiled kernels.
 //
 // Work split: a wavefront owns R query rows of one (b, h) and one key range
-// (split).  Lane t walks keys k0+t, k0+t+64, ... and runs the recurrence of Alg. 3
+// (split); the 4 wavefronts of a workgroup share the K and V tiles in LDS.
+// Lane t walks keys k0+t, k0+t+64, ... and runs the recurrence of Alg. 3
 // over ITS subsequence with the state (s_prev, ln w_prev, o) in registers, exactly
 // as the algorithm box states it.  The 64 lane states are then folded pairwise by
 // the same sigmoid rule (a run of keys acts as one key with score
@@ -15,16 +16,63 @@ namespace flashd {
 
 template <int D> struct PerKeyCfg { static constexpr int R = (D <= 64) ? 2 : 1; };
 constexpr int kPerKeyWaves = 4;
+constexpr int kPerKeyTile = kWave;            // keys per tile: one per lane
 
+typedef uint32_t pk_u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes of storage -> fp32 values (4 for fp32 storage, 8 for the 16-bit types)
+template <typename T> struct Chunk;
+template <> struct Chunk<F32> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) out[t] = __uint_as_float(w[t]);
+    }
+};
+template <> struct Chunk<BF16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[8]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            out[2 * t] = __uint_as_float(w[t] << 16);
+            out[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Chunk<F16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[8]) {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        const h8 a = __builtin_bit_cast(h8, w);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t] = static_cast<float>(a[t]);
+    }
+};
+
+// A workgroup of 4 wavefronts owns 4 R query rows of one (b, h) and one key range.  K and V
+// go through LDS in tiles of 64 keys, fetched once per workgroup in coalesced 16-byte chunks
+// (each lane reading its own key row straight from global memory touches 64 cache lines per
+// load instruction, and every row of the workgroup would fetch the tile again: that traffic,
+// not the arithmetic, set the pace).  The next tile is requested into registers before the
+// current one is worked on.  Chunk c of key row r sits at chunk position c ^ (r % 8), so that
+// the 64 lanes, each reading chunk c of its own row, spread over all banks.
 template <typename T, int D>
 __global__ __launch_bounds__(kPerKeyWaves * kWave)
 void perkey_kernel(Problem p) {
     constexpr int R = PerKeyCfg<D>::R;
     constexpr int ROWS_PER_BLOCK = R * kPerKeyWaves;
+    constexpr int EPC = Chunk<T>::N;                     // elements per 16-byte chunk
+    constexpr int CPR = D / EPC;                         // chunks per key row
+    constexpr int kThreads = kPerKeyWaves * kWave;
+    constexpr int NCH = kPerKeyTile * CPR / kThreads;    // chunks per thread, tensor and tile
+    static_assert(kPerKeyTile * CPR % kThreads == 0 && CPR % 8 == 0, "tile does not divide");
     __shared__ float lds[ROWS_PER_BLOCK][D];
+    __shared__ __align__(16) pk_u32x4 kt[kPerKeyTile * CPR];
+    __shared__ __align__(16) pk_u32x4 vt[kPerKeyTile * CPR];
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
     const int row_blocks = (p.Lq + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     const int rb = blockIdx.x % row_blocks;
     const int sp = blockIdx.x / row_blocks;
@@ -32,7 +80,6 @@ void perkey_kernel(Problem p) {
     const int b = blockIdx.z;
     const int kvh = h / (p.Hq / p.Hkv);
     const int i0 = rb * ROWS_PER_BLOCK + wave * R;
-    if (i0 >= p.Lq) return;           // no barrier below: waves are independent
 
     const size_t qbase = ((size_t)b * p.Hq + h) * (size_t)p.Lq * D;
     const size_t kbase = ((size_t)b * p.Hkv + kvh) * (size_t)p.Lk * D;
@@ -49,18 +96,16 @@ void perkey_kernel(Problem p) {
     // key range of this split, and how many keys each row may see
     const int chunk = (p.Lk + p.splits - 1) / p.splits;
     const int k0 = sp * chunk;
-    int k1 = min(p.Lk, k0 + chunk);
+    const int k1 = min(p.Lk, k0 + chunk);
+    auto visible = [&](int i) {
+        if (i >= p.Lq) return 0;
+        return p.causal ? min(max(i + p.shift + 1, 0), p.Lk) : p.Lk;
+    };
     int nvis[R];
-    int kend = 0;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int i = i0 + r;
-        int n = p.Lk;
-        if (p.causal) n = min(max(i + p.shift + 1, 0), p.Lk);
-        if (i >= p.Lq) n = 0;
-        nvis[r] = min(n, k1);
-        kend = max(kend, nvis[r]);
-    }
+    for (int r = 0; r < R; ++r) nvis[r] = min(visible(i0 + r), k1);
+    // the workgroup walks the tiles that any of its rows can see (its last row sees the most)
+    const int kend = min(visible(min(rb * ROWS_PER_BLOCK + ROWS_PER_BLOCK, p.Lq) - 1), k1);
 
     float o[R][D];
     float s_prev[R], lnw[R];
@@ -72,46 +117,83 @@ void perkey_kernel(Problem p) {
         for (int t = 0; t < D; ++t) o[r][t] = 0.0f;
     }
 
-    for (int j = k0 + lane; j < kend; j += kWave) {
-        const size_t krow = kbase + (size_t)j * D;
-        float s[R];
+    const char* kg = static_cast<const char*>(p.k) + kbase * sizeof(typename T::raw);
+    const char* vg = static_cast<const char*>(p.v) + kbase * sizeof(typename T::raw);
+    pk_u32x4 kreg[NCH], vreg[NCH];
+    auto fetch = [&](int jt) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) s[r] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < D / 8; ++c) {
-            float kk[8];
-            Store<T>::load8(p.k, krow + c * 8, kk);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int t = 0; t < 8; ++t) s[r] = fmaf(qs[r][c * 8 + t], kk[t], s[r]);
+        for (int n = 0; n < NCH; ++n) {
+            const int ci = tid + kThreads * n;           // chunk of the tile, row-major
+            const int row = ci / CPR;
+            const int c = ci % CPR;
+            const size_t off = ((size_t)min(jt + row, p.Lk - 1) * CPR + c) * 16;
+            kreg[n] = *reinterpret_cast<const pk_u32x4*>(kg + off);
+            vreg[n] = *reinterpret_cast<const pk_u32x4*>(vg + off);
         }
-        float w[R];
-        bool vis[R];
+    };
+    auto stash = [&]() {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            vis[r] = j < nvis[r];
-            const float sj = p.scale * s[r];
-            float wi = 1.0f, lw = 0.0f;                 // first key: w_1 = 1
-            if (has[r]) sigmoid_and_log(sj - s_prev[r] + lnw[r], wi, lw);
-            if (vis[r]) { w[r] = wi; lnw[r] = lw; s_prev[r] = sj; has[r] = true; }
-            else w[r] = 0.0f;                           // a masked key is not an iteration
+        for (int n = 0; n < NCH; ++n) {
+            const int ci = tid + kThreads * n;
+            const int row = ci / CPR;
+            const int c = ci % CPR;
+            kt[row * CPR + (c ^ (row & 7))] = kreg[n];
+            vt[row * CPR + (c ^ (row & 7))] = vreg[n];
         }
+    };
+
+    if (k0 < kend) fetch(k0);
+    for (int jt = k0; jt < kend; jt += kPerKeyTile) {
+        stash();
+        __syncthreads();
+        if (jt + kPerKeyTile < kend) fetch(jt + kPerKeyTile);
+        const int j = jt + lane;                         // this lane's key
+        if (i0 < p.Lq) {
+            float s[R];
 #pragma unroll
-        for (int c = 0; c < D / 8; ++c) {
-            float vv[8];
-            Store<T>::load8(p.v, krow + c * 8, vv);
+            for (int r = 0; r < R; ++r) s[r] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (vis[r]) {
+            for (int c = 0; c < CPR; ++c) {
+                float kk[EPC];
+                Chunk<T>::unpack(kt[lane * CPR + (c ^ (lane & 7))], kk);
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        float& acc = o[r][c * 8 + t];
-                        acc = fmaf(vv[t] - acc, w[r], acc);   // o + (v - o) w
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int t = 0; t < EPC; ++t) s[r] = fmaf(qs[r][c * EPC + t], kk[t], s[r]);
+                // keep the chunks apart: scheduled together, all of a row's chunks are held
+                // in registers at once, beside the 128 of the output state
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            float w[R];
+            bool vis[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                vis[r] = j < nvis[r];
+                const float sj = p.scale * s[r];
+                float wi = 1.0f, lw = 0.0f;                 // first key: w_1 = 1
+                if (has[r]) sigmoid_and_log(sj - s_prev[r] + lnw[r], wi, lw);
+                if (vis[r]) { w[r] = wi; lnw[r] = lw; s_prev[r] = sj; has[r] = true; }
+                else w[r] = 0.0f;                           // a masked key is not an iteration
+            }
+#pragma unroll
+            for (int c = 0; c < CPR; ++c) {
+                float vv[EPC];
+                Chunk<T>::unpack(vt[lane * CPR + (c ^ (lane & 7))], vv);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    if (vis[r]) {
+#pragma unroll
+                        for (int t = 0; t < EPC; ++t) {
+                            float& acc = o[r][c * EPC + t];
+                            acc = fmaf(vv[t] - acc, w[r], acc);   // o + (v - o) w
+                        }
                     }
-                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+        __syncthreads();
     }
+    if (i0 >= p.Lq) return;
 
     // fold the 64 lane states; the lower lane's keys come first
 #pragma unroll
