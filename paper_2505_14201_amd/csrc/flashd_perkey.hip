@@ -22,8 +22,12 @@ typedef uint32_t pk_u32x4 __attribute__((ext_vector_type(4)));
 
 // 16 bytes of storage -> fp32 values (4 for fp32 storage, 8 for the 16-bit types)
 template <typename T> struct Chunk;
+typedef __bf16 pk_bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 pk_f16x2 __attribute__((ext_vector_type(2)));
+
 template <> struct Chunk<F32> {
     static constexpr int N = 4;
+    static constexpr bool kPairs = false;        // scores by fma on the widened values
     static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[4]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) out[t] = __uint_as_float(w[t]);
@@ -31,6 +35,13 @@ template <> struct Chunk<F32> {
 };
 template <> struct Chunk<BF16> {
     static constexpr int N = 8;
+    // Scores of the 16-bit types: q and k stay packed, two products per v_dot2 (exact
+    // products, fp32 accumulation, subnormals kept), no widening of K
+    static constexpr bool kPairs = true;
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pk_bf16x2, a),
+                                               __builtin_bit_cast(pk_bf16x2, b), c, false);
+    }
     static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[8]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -41,6 +52,11 @@ template <> struct Chunk<BF16> {
 };
 template <> struct Chunk<F16> {
     static constexpr int N = 8;
+    static constexpr bool kPairs = true;
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(pk_f16x2, a),
+                                      __builtin_bit_cast(pk_f16x2, b), c, false);
+    }
     static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[8]) {
         typedef _Float16 h8 __attribute__((ext_vector_type(8)));
         const h8 a = __builtin_bit_cast(h8, w);
@@ -67,6 +83,7 @@ void perkey_kernel(Problem p) {
     constexpr int NCH = kPerKeyTile * CPR / kThreads;    // chunks per thread, tensor and tile
     static_assert(kPerKeyTile * CPR % kThreads == 0 && CPR % 8 == 0, "tile does not divide");
     __shared__ float lds[ROWS_PER_BLOCK][D];
+    __shared__ uint32_t qpairs[ROWS_PER_BLOCK][D / 2];      // q as stored, two per word (16-bit types)
     __shared__ __align__(16) pk_u32x4 kt[kPerKeyTile * CPR];
     __shared__ __align__(16) pk_u32x4 vt[kPerKeyTile * CPR];
 
@@ -91,7 +108,13 @@ void perkey_kernel(Problem p) {
         const int i = i0 + r;
         for (int t = lane; t < D; t += kWave)
             qs[r][t] = (i < p.Lq) ? Store<T>::load(p.q, qbase + (size_t)i * D + t) : 0.0f;
+        if constexpr (Chunk<T>::kPairs) {
+            const uint32_t* qw = static_cast<const uint32_t*>(p.q) + (qbase + (size_t)i * D) / 2;
+            for (int t = lane; t < D / 2; t += kWave)
+                qpairs[wave * R + r][t] = (i < p.Lq) ? qw[t] : 0u;
+        }
     }
+    const uint32_t (*qp)[D / 2] = &qpairs[wave * R];
 
     // key range of this split, and how many keys each row may see
     const int chunk = (p.Lk + p.splits - 1) / p.splits;
@@ -150,19 +173,41 @@ void perkey_kernel(Problem p) {
         const int j = jt + lane;                         // this lane's key
         if (i0 < p.Lq) {
             float s[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) s[r] = 0.0f;
-#pragma unroll
-            for (int c = 0; c < CPR; ++c) {
-                float kk[EPC];
-                Chunk<T>::unpack(kt[lane * CPR + (c ^ (lane & 7))], kk);
+            if constexpr (Chunk<T>::kPairs) {
+                float part[R][4];                // four chains per row, added at the end
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int t = 0; t < EPC; ++t) s[r] = fmaf(qs[r][c * EPC + t], kk[t], s[r]);
-                // keep the chunks apart: scheduled together, all of a row's chunks are held
-                // in registers at once, beside the 128 of the output state
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int t = 0; t < 4; ++t) part[r][t] = 0.0f;
+#pragma unroll
+                for (int c = 0; c < CPR; ++c) {
+                    const pk_u32x4 kw = kt[lane * CPR + (c ^ (lane & 7))];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            part[r][t] = Chunk<T>::dot2(kw[t], qp[r][4 * c + t], part[r][t]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    s[r] = (part[r][0] + part[r][1]) + (part[r][2] + part[r][3]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) s[r] = 0.0f;
+#pragma unroll
+                for (int c = 0; c < CPR; ++c) {
+                    float kk[EPC];
+                    Chunk<T>::unpack(kt[lane * CPR + (c ^ (lane & 7))], kk);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int t = 0; t < EPC; ++t)
+                            s[r] = fmaf(qs[r][c * EPC + t], kk[t], s[r]);
+                    // keep the chunks apart: scheduled together, all of a row's chunks are
+                    // held in registers at once, beside the 128 of the output state
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             float w[R];
             bool vis[R];
