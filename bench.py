@@ -27,7 +27,7 @@ PEAK_FP32_FMA = 78.6
 # HBM-side bytes per launch of the dominant kernel, from the profiler's FETCH_SIZE and
 # WRITE_SIZE counters scaled by a 1 GiB device copy (the summaries under profiles/ give the
 # commands and the raw readings); they cannot be read from inside this process.
-TRAFFIC_PREFILL_BYTES = 342.7e6
+TRAFFIC_PREFILL_BYTES = 343.8e6
 TRAFFIC_DECODE_BYTES = 2148.6e6
 
 
