@@ -387,3 +387,23 @@ def test_query_heads_of_a_kv_group_run_as_one_head(shape, causal, variant, dtype
     check(got, ref, DT[dtype], f"{shape} causal={causal} {dtype} d={d} v={variant} s={splits}")
     if causal and Lq > Lk:
         assert torch.count_nonzero(got[:, :, :Lq - Lk]) == 0, "rows without keys must be zeros"
+
+
+@pytest.mark.parametrize("shape,variant,dtype", [
+    ((2, 8, 2, 1, 5000), TILE, "bf16"),        # decode kernel, 64 partials per row
+    ((1, 4, 4, 150, 4500), TILE, "f16"),       # tile kernel
+    ((1, 8, 2, 12, 4100), ONLINE, "bf16"),     # heads of a kv group as one head
+    ((1, 2, 1, 9, 4200), PER_KEY, "f32"),
+    ((1, 2, 2, 3, 64), PER_KEY, "bf16"),       # one key per split
+])
+@pytest.mark.parametrize("causal", [False, True])
+def test_maximum_number_of_splits(shape, variant, dtype, causal):
+    """64 splits (FLASHD_MAX_SPLITS): every lane of the merging wavefront holds a partial;
+    under a causal mask many of them are empty."""
+    B, Hq, Hkv, Lq, Lk = shape
+    w = synthetic.small("max splits", B, Hq, Hkv, Lq, Lk, 128, dtype, causal, seed=9100 + Lk)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, causal, w.scale)
+    got = run_flashd(q, k, v, causal, w.scale, variant, 64)
+    check(got, ref, DT[dtype], f"{shape} {dtype} variant={variant} causal={causal}",
+          smax=max_abs_score(q, k, w.scale))
