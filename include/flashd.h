@@ -147,6 +147,26 @@ int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o,
                         void* stream);
 
 /*
+ * flashd_attn_fwd for callers that cannot allocate: work recorded into a HIP graph, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same choice of variant and
+ * splits, same result bit for bit; the split-K partial states go into a fixed array of
+ * FLASHD_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the library
+ * runs on holds one copy until the process ends) instead of the grow-only cache.  Calls no
+ * hipMalloc, hipFree or other allocating routine.  A problem whose partial states
+ * (flashd_workspace_bytes(..., FLASHD_VARIANT_AUTO, 0)) exceed that size is refused with
+ * FLASHD_E_WORKSPACE and nothing is enqueued: use flashd_attn_fwd_ex with memory of your own
+ * for it.  All calls on one GPU share the array, whatever their stream, and it keeps the last
+ * call's contents (every partial state a call reads it has written first, so nothing needs
+ * clearing): calls that overlap in time on one GPU race; order them on one stream or by events.
+ * The first call on a device looks up the array's device address (which may load the code
+ * object); make that call outside a graph capture.
+ */
+#define FLASHD_STATIC_SCRATCH_BYTES (32u << 20)
+int flashd_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
+                           int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                           int causal, float scale, int dtype, void* stream);
+
+/*
  * Static skip statistics (Sec. III-C; the quantity reported in Table I).  Over every query
  * row and every step i >= 2 of Alg. 3 on that row's visible keys (same layout, head mapping
  * and causal rule as above; v is not needed), counts

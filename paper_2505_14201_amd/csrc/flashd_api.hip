@@ -137,6 +137,35 @@ int cached_workspace(void* stream, size_t bytes, void** out) {
     return FLASHD_OK;
 }
 
+// ---- static scratch: split-K partial states for the entry point that allocates nothing ---
+// One array per GPU, part of the loaded code object, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress: the device address is asked
+// for once per device (with that device current) and kept, and only that address is ever
+// handed to a kernel.
+constexpr size_t kScratchBytes = FLASHD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+std::map<int, void*> g_scratch_ptr;     // device -> address of its copy of `scratch`
+
+int static_scratch(void** out) {
+    *out = nullptr;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_scratch_ptr.find(dev);
+    if (it == g_scratch_ptr.end()) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return FLASHD_E_HIP;
+        }
+        it = g_scratch_ptr.emplace(dev, ptr).first;
+    }
+    *out = it->second;
+    return FLASHD_OK;
+}
+
+enum class WsMode { Caller, Cache, Static };
+
 // ---- common front end --------------------------------------------------------
 
 struct StateArgs {
@@ -153,8 +182,9 @@ struct Kv8Args {
 
 int run(const void* q, const void* k, const void* v, void* o, const Shape& s, int causal,
         float scale, void* stream, int variant, int splits, void* workspace,
-        size_t workspace_bytes, bool use_cache, const StateArgs& sa = StateArgs(),
+        size_t workspace_bytes, WsMode mode, const StateArgs& sa = StateArgs(),
         const Kv8Args& k8 = Kv8Args()) {
+    const bool use_cache = mode == WsMode::Cache;
     if (!q || !k || !v) return FLASHD_E_NULL;
     if (!o && !(sa.on && sa.out)) return FLASHD_E_NULL;
     int rc = validate_shape(s);
@@ -178,8 +208,9 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     const bool in_kernel = sa.on && sp == 1 && var == FLASHD_VARIANT_TILE &&
                            !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
     const size_t need = sa.on ? ((direct || in_kernel) ? 0 : partial_bytes(s, sp)) : ws_bytes(s, sp);
-    if (!use_cache && need > 0 && (workspace == nullptr || workspace_bytes < need))
+    if (mode == WsMode::Caller && need > 0 && (workspace == nullptr || workspace_bytes < need))
         return FLASHD_E_WORKSPACE;
+    if (mode == WsMode::Static && need > kScratchBytes) return FLASHD_E_WORKSPACE;
 
     rc = check_arch();
     if (rc != FLASHD_OK) return rc;
@@ -188,6 +219,10 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     const size_t kv_bytes = widen ? (size_t)s.B * s.Hkv * s.Lk * s.d * 2 : 0;   // per tensor
     if (use_cache) {
         rc = cached_workspace(stream, need_al + 2 * kv_bytes, &ws);
+        if (rc != FLASHD_OK) return rc;
+    }
+    if (mode == WsMode::Static && need > 0) {
+        rc = static_scratch(&ws);
         if (rc != FLASHD_OK) return rc;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -251,7 +286,16 @@ extern "C" {
 int flashd_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv,
                     int Lq, int Lk, int d, int causal, float scale, int dtype, void* stream) {
     const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
-    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true);
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0,
+               WsMode::Cache);
+}
+
+int flashd_attn_fwd_static(const void* q, const void* k, const void* v, void* o, int B, int Hq,
+                           int Hkv, int Lq, int Lk, int d, int causal, float scale, int dtype,
+                           void* stream) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0,
+               WsMode::Static);
 }
 
 int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B, int Hq,
@@ -260,7 +304,7 @@ int flashd_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int
                        size_t workspace_bytes) {
     const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
     return run(q, k, v, o, s, causal, scale, stream, variant, splits, workspace, workspace_bytes,
-               false);
+               WsMode::Caller);
 }
 
 int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
@@ -273,7 +317,8 @@ int flashd_attn_fwd_state(const void* q, const void* k, const void* v, void* o,
     sa.shift = causal_shift;
     sa.in = state_in;
     sa.out = state_out;
-    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true, sa);
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0,
+               WsMode::Cache, sa);
 }
 
 int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o, int B, int Hq,
@@ -284,8 +329,8 @@ int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o, 
     a.on = true;
     a.kscale = kscale;
     a.vscale = vscale;
-    return run(q, k8, v8, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0, true,
-               StateArgs(), a);
+    return run(q, k8, v8, o, s, causal, scale, stream, FLASHD_VARIANT_AUTO, 0, nullptr, 0,
+               WsMode::Cache, StateArgs(), a);
 }
 
 int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,

@@ -18,12 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libflashd.so")
 F32, F16, BF16 = 0, 1, 2
 VARIANT_AUTO, VARIANT_TILE, VARIANT_PER_KEY, VARIANT_ONLINE_SOFTMAX = 0, 1, 2, 3
 MAX_SPLITS = 64
+STATIC_SCRATCH_BYTES = 32 << 20
 
 _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
            "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
-           "flashd_attn_fwd_kv8")
+           "flashd_attn_fwd_kv8", "flashd_attn_fwd_static")
 
 
 class FlashdError(RuntimeError):
@@ -42,6 +43,8 @@ def _load() -> ctypes.CDLL:
     base = [p, p, p, p, i, i, i, i, i, i, i, f, i, p]
     lib.flashd_attn_fwd.restype = i
     lib.flashd_attn_fwd.argtypes = base
+    lib.flashd_attn_fwd_static.restype = i
+    lib.flashd_attn_fwd_static.argtypes = base
     lib.flashd_attn_fwd_ex.restype = i
     lib.flashd_attn_fwd_ex.argtypes = base + [i, i, p, z]
     lib.flashd_workspace_bytes.restype = z
@@ -114,6 +117,19 @@ def attn_fwd(q, k, v, o, causal: bool, scale: float, stream=None) -> None:
         st = _stream_ptr(stream)
         rc = _lib.flashd_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                   B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale), dt, st)
+    if rc != 0:
+        raise FlashdError(rc)
+
+
+def attn_fwd_static(q, k, v, o, causal: bool, scale: float, stream=None) -> None:
+    """flashd_attn_fwd_static: as attn_fwd, split-K scratch in the library's fixed array
+    (no allocation; raises FlashdError(E_WORKSPACE) when the problem needs more)."""
+    B, Hq, Hkv, Lq, Lk, d, dt = _marshal(q, k, v, o)
+    with torch.cuda.device(q.device):
+        st = _stream_ptr(stream)
+        rc = _lib.flashd_attn_fwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                         B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale),
+                                         dt, st)
     if rc != 0:
         raise FlashdError(rc)
 
