@@ -114,7 +114,9 @@ int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
  *   state_in   DEVICE pointer or NULL (no earlier keys): [B][Hq][Lq][d + 2] fp32, per query
  *              row (o[0..d), s, ln w).  A row that has seen no key has s = -inf, ln w = 0.
  *   state_out  DEVICE pointer or NULL: same layout, receives the state after this call's keys,
- *              normalised to (o, s = s_last - ln w_last, ln w = 0).  May equal state_in.
+ *              normalised to (o, s = s_last - ln w_last, ln w = 0); with fp32 storage ln w
+ *              holds what s - ln w needs beyond one float instead of 0 (only the difference
+ *              enters later steps).  May equal state_in.
  *   o          DEVICE pointer or NULL: the attention output after this call's keys in the
  *              storage type (what the state's o holds).  o and state_out must not both be NULL.
  *   causal_shift  with causal != 0, key j of THIS call is visible to query i iff

@@ -142,6 +142,22 @@ __device__ __forceinline__ void sigmoid_and_log(float x, float& w, float& lnw) {
     lnw = pos ? -lt : x - lt;
 }
 
+// The same step with the argument and the logarithm carried in fp64 (fp32 storage: scores of
+// several hundred have an fp32 spacing of 6e-5, which as an error of s - ln w is a relative
+// error of every later weight; the stated fp32 tolerance is 1e-5).  Only sums and differences
+// of large terms are fp64; the exponential and the logarithm see a rounded argument whose
+// error no longer matters (|x| <= 104 wherever e is not zero, and ln(1 + e) <= ln 2).
+__device__ __forceinline__ void sigmoid_and_log(double x, float& w, double& lnw) {
+    const float xf = static_cast<float>(x);
+    float e = __expf(-fabsf(xf));
+    float t = 1.0f + e;
+    float r = __frcp_rn(t);
+    float lt = __logf(t);
+    bool pos = x >= 0.0;
+    w = pos ? r : e * r;
+    lnw = pos ? -static_cast<double>(lt) : x - static_cast<double>(lt);
+}
+
 // A run of keys is summarised by (o, lam) with lam = s_last - ln w_last; the empty
 // run has lam = -inf.  Appending run B to run A treats B as one key of score lam_b
 // and value o_b: W = sigmoid(lam_b - lam_a), o = o_a + (o_b - o_a) W (Sec. IV-A
@@ -153,6 +169,22 @@ __device__ __forceinline__ void merge_weight(float lam_a, float lam_b, float& W,
     float lnW;
     sigmoid_and_log(lam_b - lam_a, W, lnW);
     lam = lam_b - lnW;
+}
+__device__ __forceinline__ void merge_weight(double lam_a, double lam_b, float& W, double& lam) {
+    const double ninf = -__builtin_inf();
+    if (lam_b == ninf) { W = 0.0f; lam = lam_a; return; }
+    if (lam_a == ninf) { W = 1.0f; lam = lam_b; return; }
+    double lnW;
+    sigmoid_and_log(lam_b - lam_a, W, lnW);
+    lam = lam_b - lnW;
+}
+
+// A state's (s, ln w) pair as two floats whose difference is lam: fp32 storage keeps what
+// lam needs beyond one float in ln w (only s - ln w enters later steps).
+__device__ __forceinline__ void split_lam(float lam, float& s, float& lnw) { s = lam; lnw = 0.0f; }
+__device__ __forceinline__ void split_lam(double lam, float& s, float& lnw) {
+    s = static_cast<float>(lam);
+    lnw = (s == -__builtin_inff()) ? 0.0f : static_cast<float>(static_cast<double>(s) - lam);
 }
 
 }  // namespace flashd

@@ -12,6 +12,8 @@
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 
+#include <type_traits>
+
 namespace flashd {
 
 template <int D> struct PerKeyCfg { static constexpr int R = (D <= 64) ? 2 : 1; };
@@ -28,6 +30,10 @@ typedef _Float16 pk_f16x2 __attribute__((ext_vector_type(2)));
 template <> struct Chunk<F32> {
     static constexpr int N = 4;
     static constexpr bool kPairs = false;        // scores by fma on the widened values
+    // fp32 storage: the dot product, the score and s - ln w are carried in fp64 (same fma
+    // rate as unpacked fp32 on this part), so that the stated 1e-5 holds whatever the size
+    // of the scores; weights and the blend of Alg. 3 stay fp32
+    using state_t = double;
     static __device__ __forceinline__ void unpack(pk_u32x4 w, float (&out)[4]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) out[t] = __uint_as_float(w[t]);
@@ -35,6 +41,7 @@ template <> struct Chunk<F32> {
 };
 template <> struct Chunk<BF16> {
     static constexpr int N = 8;
+    using state_t = float;
     // Scores of the 16-bit types: q and k stay packed, two products per v_dot2 (exact
     // products, fp32 accumulation, subnormals kept), no widening of K
     static constexpr bool kPairs = true;
@@ -52,6 +59,7 @@ template <> struct Chunk<BF16> {
 };
 template <> struct Chunk<F16> {
     static constexpr int N = 8;
+    using state_t = float;
     static constexpr bool kPairs = true;
     static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
         return __builtin_amdgcn_fdot2(__builtin_bit_cast(pk_f16x2, a),
@@ -82,7 +90,10 @@ void perkey_kernel(Problem p) {
     constexpr int kThreads = kPerKeyWaves * kWave;
     constexpr int NCH = kPerKeyTile * CPR / kThreads;    // chunks per thread, tensor and tile
     static_assert(kPerKeyTile * CPR % kThreads == 0 && CPR % 8 == 0, "tile does not divide");
+    using state_t = typename Chunk<T>::state_t;
+    constexpr bool kWide = std::is_same<state_t, double>::value;
     __shared__ float lds[ROWS_PER_BLOCK][D];
+    __shared__ double qwide[kWide ? ROWS_PER_BLOCK : 1][kWide ? D : 1];   // q widened once
     __shared__ uint32_t qpairs[ROWS_PER_BLOCK][D / 2];      // q as stored, two per word (16-bit types)
     __shared__ __align__(16) pk_u32x4 kt[kPerKeyTile * CPR];
     __shared__ __align__(16) pk_u32x4 vt[kPerKeyTile * CPR];
@@ -108,6 +119,8 @@ void perkey_kernel(Problem p) {
         const int i = i0 + r;
         for (int t = lane; t < D; t += kWave)
             qs[r][t] = (i < p.Lq) ? Store<T>::load(p.q, qbase + (size_t)i * D + t) : 0.0f;
+        if constexpr (kWide)
+            for (int t = lane; t < D; t += kWave) qwide[wave * R + r][t] = (double)qs[r][t];
         if constexpr (Chunk<T>::kPairs) {
             const uint32_t* qw = static_cast<const uint32_t*>(p.q) + (qbase + (size_t)i * D) / 2;
             for (int t = lane; t < D / 2; t += kWave)
@@ -131,11 +144,11 @@ void perkey_kernel(Problem p) {
     const int kend = min(visible(min(rb * ROWS_PER_BLOCK + ROWS_PER_BLOCK, p.Lq) - 1), k1);
 
     float o[R][D];
-    float s_prev[R], lnw[R];
+    state_t s_prev[R], lnw[R];
     bool has[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        s_prev[r] = 0.0f; lnw[r] = 0.0f; has[r] = false;
+        s_prev[r] = 0; lnw[r] = 0; has[r] = false;
 #pragma unroll
         for (int t = 0; t < D; ++t) o[r][t] = 0.0f;
     }
@@ -172,7 +185,7 @@ void perkey_kernel(Problem p) {
         if (jt + kPerKeyTile < kend) fetch(jt + kPerKeyTile);
         const int j = jt + lane;                         // this lane's key
         if (i0 < p.Lq) {
-            float s[R];
+            state_t s[R];
             if constexpr (Chunk<T>::kPairs) {
                 float part[R][4];                // four chains per row, added at the end
 #pragma unroll
@@ -193,8 +206,9 @@ void perkey_kernel(Problem p) {
                 for (int r = 0; r < R; ++r)
                     s[r] = (part[r][0] + part[r][1]) + (part[r][2] + part[r][3]);
             } else {
+                const double (*qd)[kWide ? D : 1] = &qwide[kWide ? wave * R : 0];
 #pragma unroll
-                for (int r = 0; r < R; ++r) s[r] = 0.0f;
+                for (int r = 0; r < R; ++r) s[r] = 0;
 #pragma unroll
                 for (int c = 0; c < CPR; ++c) {
                     float kk[EPC];
@@ -202,8 +216,10 @@ void perkey_kernel(Problem p) {
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int t = 0; t < EPC; ++t)
-                            s[r] = fmaf(qs[r][c * EPC + t], kk[t], s[r]);
+                        for (int t = 0; t < EPC; ++t) {
+                            if constexpr (kWide) s[r] = fma(qd[r][c * EPC + t], (double)kk[t], s[r]);
+                            else s[r] = fmaf(qs[r][c * EPC + t], kk[t], s[r]);
+                        }
                     // keep the chunks apart: scheduled together, all of a row's chunks are
                     // held in registers at once, beside the 128 of the output state
                     __builtin_amdgcn_sched_barrier(0);
@@ -214,8 +230,9 @@ void perkey_kernel(Problem p) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 vis[r] = j < nvis[r];
-                const float sj = p.scale * s[r];
-                float wi = 1.0f, lw = 0.0f;                 // first key: w_1 = 1
+                const state_t sj = (state_t)p.scale * s[r];
+                float wi = 1.0f;
+                state_t lw = 0;                             // first key: w_1 = 1
                 if (has[r]) sigmoid_and_log(sj - s_prev[r] + lnw[r], wi, lw);
                 if (vis[r]) { w[r] = wi; lnw[r] = lw; s_prev[r] = sj; has[r] = true; }
                 else w[r] = 0.0f;                           // a masked key is not an iteration
@@ -243,14 +260,15 @@ void perkey_kernel(Problem p) {
     // fold the 64 lane states; the lower lane's keys come first
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        float lam = has[r] ? s_prev[r] - lnw[r] : -__builtin_inff();
+        state_t lam = has[r] ? s_prev[r] - lnw[r] : (state_t)(-__builtin_inff());
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             const bool upper = (lane & off) != 0;
-            const float lam_x = __shfl_xor(lam, off, kWave);
-            const float lam_a = upper ? lam_x : lam;
-            const float lam_b = upper ? lam : lam_x;
-            float W, lam_n;
+            const state_t lam_x = __shfl_xor(lam, off, kWave);
+            const state_t lam_a = upper ? lam_x : lam;
+            const state_t lam_b = upper ? lam : lam_x;
+            float W;
+            state_t lam_n;
             merge_weight(lam_a, lam_b, W, lam_n);
 #pragma unroll
             for (int t = 0; t < D; ++t) {
@@ -275,7 +293,7 @@ void perkey_kernel(Problem p) {
             // partial state (o, s, ln w): the run acts as one key of score lam, weight 1
             float* dst = p.ws + ((((size_t)sp * p.B + b) * p.Hq + h) * (size_t)p.Lq + i) * (D + 2);
             for (int t = lane; t < D; t += kWave) dst[t] = qs[r][t];
-            if (lane == 0) { dst[D] = lam; dst[D + 1] = 0.0f; }
+            if (lane == 0) split_lam(lam, dst[D], dst[D + 1]);
         }
     }
 }
@@ -300,7 +318,8 @@ template <typename T, int D, int kBatch>            // kBatch: partial rows in f
 __global__ __launch_bounds__(256)
 void merge_splits_kernel(Problem p) {
     constexpr int E = D / kWave;                   // output elements per lane
-    const float ninf = -__builtin_inff();
+    using state_t = typename Chunk<T>::state_t;    // fp32 storage folds s - ln w in fp64
+    const state_t ninf = (state_t)(-__builtin_inff());
     const size_t rows = (size_t)p.B * p.Hq * p.Lq;
     const int lane = threadIdx.x & (kWave - 1);
     const size_t row = (size_t)blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
@@ -319,25 +338,25 @@ void merge_splits_kernel(Problem p) {
         }
     };
     fetch(0);
-    float lam_p = ninf;
+    state_t lam_p = ninf;
     if (lane < p.splits) {
         const float* src = p.ws + ((size_t)lane * rows + row) * (D + 2);
-        lam_p = src[D] - src[D + 1];               // s - ln w
+        lam_p = (state_t)src[D] - (state_t)src[D + 1];               // s - ln w
     }
-    float lam_in = ninf;
+    state_t lam_in = ninf;
     float oin[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) oin[e] = 0.0f;
     if (p.state_in) {
         const float* sin = p.state_in + row * (D + 2);
-        lam_in = sin[D] - sin[D + 1];
+        lam_in = (state_t)sin[D] - (state_t)sin[D + 1];
 #pragma unroll
         for (int e = 0; e < E; ++e) oin[e] = sin[lane * E + e];
     }
-    float tot = lam_p;
+    state_t tot = lam_p;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-        const float other = __shfl_xor(tot, off);
+        const state_t other = __shfl_xor(tot, off);
         const bool upper = (lane & off) != 0;      // both lanes of a pair fold (lower, upper)
         float W;
         merge_weight(upper ? other : tot, upper ? tot : other, W, tot);
@@ -346,8 +365,8 @@ void merge_splits_kernel(Problem p) {
         float W;
         merge_weight(lam_in, tot, W, tot);
     }
-    const float w_p = lam_p == ninf ? 0.0f : __expf(lam_p - tot);
-    const float w_in = lam_in == ninf ? 0.0f : __expf(lam_in - tot);
+    const float w_p = lam_p == ninf ? 0.0f : __expf((float)(lam_p - tot));
+    const float w_in = lam_in == ninf ? 0.0f : __expf((float)(lam_in - tot));
 
     float acc[E];
 #pragma unroll
@@ -371,7 +390,7 @@ void merge_splits_kernel(Problem p) {
         float* dst = p.state_out + row * (D + 2);
 #pragma unroll
         for (int e = 0; e < E; ++e) dst[lane * E + e] = acc[e];
-        if (lane == 0) { dst[D] = tot; dst[D + 1] = 0.0f; }
+        if (lane == 0) split_lam(tot, dst[D], dst[D + 1]);
     }
 }
 

@@ -9,7 +9,7 @@ import torch
 
 from oracle import attention as oa
 from paper_2505_14201_amd import synthetic
-from tests.gpu_util import check, max_abs_score, run_flashd
+from tests.gpu_util import check, run_flashd
 
 pytestmark = pytest.mark.gpu
 
@@ -205,8 +205,7 @@ def test_huge_scores_and_dominant_keys_stay_finite_and_right(variant, dtype, d, 
     assert len(planted) > 20
     ref = oracle(q, k, v, True, w.scale)
     got = run_flashd(q, k, v, True, w.scale, variant, splits)
-    check(got, ref, DT[dtype], f"stress variant={variant} {dtype}",
-          smax=max_abs_score(q, k, w.scale))
+    check(got, ref, DT[dtype], f"stress variant={variant} {dtype}")
 
 
 @pytest.mark.parametrize("dtype,step_nats", [("f16", 12.0), ("f16", 30.0), ("bf16", 45.0),
@@ -234,8 +233,7 @@ def test_staircase_scores(dtype, step_nats, Lq):
         for variant, splits in ((TILE, 1), (TILE, 2), (PER_KEY, 1)):
             got = run_flashd(qq, kk, vv, causal, 1.0, variant, splits)
             check(got, ref, DT[dtype], f"staircase {dtype} step={step_nats} Lq={Lq} "
-                                       f"causal={causal} variant={variant} splits={splits}",
-                  smax=max_abs_score(qq, kk, 1.0))
+                                       f"causal={causal} variant={variant} splits={splits}")
 
 
 def test_score_ramps():
@@ -405,5 +403,4 @@ def test_maximum_number_of_splits(shape, variant, dtype, causal):
     q, k, v, _ = synthetic.make_qkv(w)
     ref = oracle(q, k, v, causal, w.scale)
     got = run_flashd(q, k, v, causal, w.scale, variant, 64)
-    check(got, ref, DT[dtype], f"{shape} {dtype} variant={variant} causal={causal}",
-          smax=max_abs_score(q, k, w.scale))
+    check(got, ref, DT[dtype], f"{shape} {dtype} variant={variant} causal={causal}")

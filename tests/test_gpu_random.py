@@ -10,7 +10,7 @@ import torch
 
 from oracle import attention as oa
 from paper_2505_14201_amd import flashd, synthetic
-from tests.gpu_util import check, max_abs_score, run_flashd
+from tests.gpu_util import check, run_flashd
 from tests.test_gpu_state import check_state, run_chunks
 
 pytestmark = pytest.mark.gpu
@@ -47,7 +47,7 @@ def test_random_forward_calls(seed):
         what = f"seed={seed} it={it} {w} variant={variant} splits={splits}"
         ref = oa.attn(q, k, v, w.causal, w.scale)
         got = run_flashd(q, k, v, w.causal, w.scale, variant, splits)
-        check(got, ref, DT[w.dtype], what, smax=max_abs_score(q, k, w.scale))
+        check(got, ref, DT[w.dtype], what)
 
 
 @pytest.mark.parametrize("seed", [201, 202])
@@ -65,7 +65,7 @@ def test_random_chunked_calls_with_state(seed):
         what = f"seed={seed} it={it} {w} cuts={cuts}"
         ref = oa.attn_state(q, k, v, w.causal, w.scale)
         o, st = run_chunks(q, k, v, w.causal, w.scale, cuts)
-        check(o, ref[..., :w.d], DT[w.dtype], what + " (o)", smax=max_abs_score(q, k, w.scale))
+        check(o, ref[..., :w.d], DT[w.dtype], what + " (o)")
         if w.qk_std <= 1.0:       # s - ln w to the fp32 bound only where scores are ordinary
             check_state(st, ref, w.d, DT[w.dtype], what)
 

@@ -6,7 +6,7 @@ import torch
 
 from oracle import attention as oa
 from paper_2505_14201_amd import flashd, synthetic
-from tests.gpu_util import check
+from tests.gpu_util import Guarded, check
 
 pytestmark = pytest.mark.gpu
 DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
@@ -40,19 +40,23 @@ def run_chunks(q, k, v, causal, scale, cuts, in_place=False):
     Lk = k.shape[2]
     qg = q.cuda()
     st = None
-    o = torch.full_like(qg, float("nan"))
+    # the output and every state buffer sit between canaries, checked after the launches
+    guards = [Guarded(qg.numel() * qg.element_size())]
+    o = guards[0].view(qg.dtype, qg.shape)
     k0 = 0
     for k1 in list(cuts) + [Lk]:
         kc, vc = k[:, :, k0:k1].contiguous().cuda(), v[:, :, k0:k1].contiguous().cuda()
         if in_place and st is not None:
             out = st
         else:
-            out = torch.full((B, Hq, Lq, d + 2), float("nan"), dtype=torch.float32, device="cuda")
+            guards.append(Guarded(B * Hq * Lq * (d + 2) * 4))
+            out = guards[-1].view(torch.float32, (B, Hq, Lq, d + 2))
         flashd.attn_fwd_state(qg, kc, vc, causal, scale, o=o, state_in=st, state_out=out,
                               causal_shift=(Lk - Lq) - k0)
         st = out
         k0 = k1
     torch.cuda.synchronize()
+    assert all(g.intact() for g in guards), "a kernel wrote outside the output or a state buffer"
     return o.cpu(), st.cpu()
 
 
