@@ -12,6 +12,12 @@
  * w_i = sigmoid(s_i - s_{i-1} + ln w_{i-1}); there is no running maximum, no running sum of
  * exponentials and no division of the output.  Runs of keys (tiles, split-K partitions) are
  * folded by the same rule, a run acting as one key whose score is s_last - ln w_last.
+ * That is literally what PER_KEY does per key and TILE_BLEND per tile of keys.  The default
+ * matrix-core variant TILE does not apply the (1 - W) factor of each tile to the accumulator
+ * but carries their product as one scalar beta per row and multiplies it in at the store; in
+ * that form 1/beta is a sum of exponentials 2^(s_j - R) against a reference R that moves only
+ * when a score would overflow, so compared with Alg. 2 it drops the running maximum and the
+ * per-tile rescaling of the accumulator, not the sum.
  *
  * Conventions shared by every entry point
  *   - q, k, v, o and workspace are DEVICE pointers owned by the caller; the library never
@@ -59,10 +65,14 @@ typedef enum {
 /* How the recurrence is evaluated.  All variants compute the same result. */
 typedef enum {
     FLASHD_VARIANT_AUTO = 0,     /* TILE for f16/bf16, PER_KEY for f32                      */
-    FLASHD_VARIANT_TILE = 1,     /* Alg. 3 lifted to key tiles on the matrix cores (f16/bf16) */
+    FLASHD_VARIANT_TILE = 1,     /* Alg. 3 lifted to key tiles on the matrix cores (f16/bf16),
+                                    the (1 - W) factors of the blend deferred to the store   */
     FLASHD_VARIANT_PER_KEY = 2,  /* Alg. 3 literally, one sigmoid per key (any dtype)       */
-    FLASHD_VARIANT_ONLINE_SOFTMAX = 3  /* ablation: Alg. 2 (running max, sum, final division)
+    FLASHD_VARIANT_ONLINE_SOFTMAX = 3, /* ablation: Alg. 2 (running max, sum, final division)
                                           on the same tiling as TILE (f16/bf16)             */
+    FLASHD_VARIANT_TILE_BLEND = 4      /* Alg. 3 on key tiles with the blend of Sec. III-A applied
+                                          on every tile: o <- (1 - W) o + sum_j c_j v_j with
+                                          W = sigmoid(Lam_tile - Lam) and c_j <= 1 (f16/bf16)  */
 } flashd_variant;
 
 /*
@@ -78,7 +88,7 @@ int flashd_attn_fwd(const void* q, const void* k, const void* v, void* o,
 
 /*
  * Same computation with explicit knobs.
- *   variant   a flashd_variant; TILE and ONLINE_SOFTMAX need f16/bf16 (else FLASHD_E_VARIANT).
+ *   variant   a flashd_variant; TILE, TILE_BLEND and ONLINE_SOFTMAX need f16/bf16 (else FLASHD_E_VARIANT).
  *   splits    number of consecutive key ranges reduced independently and then merged with
  *             the sigmoid rule; 0 = choose, 1 = no split; at most FLASHD_MAX_SPLITS and at
  *             most Lk (else FLASHD_E_VARIANT).

@@ -34,7 +34,7 @@ int validate_shape(const Shape& s) {
 }
 
 int resolve_variant(const Shape& s, int variant) {
-    if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_ONLINE_SOFTMAX) return -1;
+    if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_TILE_BLEND) return -1;
     if (variant == FLASHD_VARIANT_AUTO)
         return s.dtype == FLASHD_F32 ? FLASHD_VARIANT_PER_KEY : FLASHD_VARIANT_TILE;
     if (s.dtype == FLASHD_F32 && variant != FLASHD_VARIANT_PER_KEY) return -1;
@@ -272,10 +272,12 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.vscale = k8.vscale;
     if (direct && !in_kernel) p.ws = sa.out;
     hipError_t e;
-    const bool online = var == FLASHD_VARIANT_ONLINE_SOFTMAX;
+    const int tmode = var == FLASHD_VARIANT_ONLINE_SOFTMAX ? flashd::kTileModeOnline
+                     : var == FLASHD_VARIANT_TILE_BLEND   ? flashd::kTileModeBlend
+                                                          : flashd::kTileModeLazy;
     if (var == FLASHD_VARIANT_PER_KEY) e = flashd::launch_perkey(p, st);
-    else if (flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) e = flashd::launch_decode(p, online, st);
-    else e = flashd::launch_tile(p, online, st);
+    else if (flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) e = flashd::launch_decode(p, tmode, st);
+    else e = flashd::launch_tile(p, tmode, st);
     return e == hipSuccess ? FLASHD_OK : FLASHD_E_HIP;
 }
 

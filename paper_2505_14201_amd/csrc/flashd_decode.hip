@@ -75,9 +75,13 @@ __device__ __forceinline__ void widen16(u32x4 raw, u32x4& lo, u32x4& hi) {
                Mma<T>::from_fp8_lo(raw[3]), Mma<T>::from_fp8_hi(raw[3])};
 }
 
-template <typename T, int D, bool ONLINE, bool KV8>
+// MODE: how a block's scores update a row (kTileModeLazy / Online / Blend).  TL: the state
+// is handed out and the coefficient sums are those of the rounded coefficients, so the
+// unrounded sum is carried as well (the Lam handed out is then the true log-sum-exp).
+template <typename T, int D, int MODE, bool KV8, bool TL>
 __global__ __launch_bounds__(kDecThreads, 2)
 void decode_kernel(Problem p) {
+    constexpr bool kTL = TL && Mma<T>::kRoundedSum && MODE == kTileModeLazy;
     constexpr int KROW = D + 8;                 // padded LDS rows (elements)
     constexpr int VROW = D + 32;                // conflict-free for the transposing read
     constexpr int NKK = D / 16;
@@ -138,9 +142,11 @@ void decode_kernel(Problem p) {
     for (int i = 0; i < NDB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) U[i][r] = 0.0f;
-    LazyRow st = {0.0f, 1.0f, 0.0f};      // FLASH-D state of the lane's row
+    LazyRow st = {0.0f, 1.0f, 0.0f, 0.0f};      // FLASH-D state of the lane's row (lazy form)
+    BlendRow bl = {0.0f, 0.0f};            // FLASH-D state, literal per-block blend
     float lam = ninf, beta = 0.0f;         // Alg. 2 state: running max, running sum
     bool first = true;
+    Wary wary = {0, kWaryTiles};     // wavefront-uniform, see lazy_spec_pack
 
     constexpr int CHR = KV8 ? CH / 2 : CH;     // 16-byte loads per lane, block and tensor
     // One block per wavefront is in flight while the previous one is multiplied.  (Two
@@ -199,33 +205,43 @@ void decode_kernel(Problem p) {
         first = false;
         const int jb = j0 + 4 * hh;
         u32x4 bfrag[2];
-        if (!ONLINE) {
-            bool risky;
-            LazySpec spec;
-            if (general) risky = lazy_spec_pack<T, 1, true, true>(acc, bfrag, st, c_log2, jb, nvis, lane, spec);
-            else risky = lazy_spec_pack<T, 1, false, false>(acc, bfrag, st, c_log2, jb, nvis, lane, spec);
-            if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-                const bool lost = risky && !(spec.psum <= kLazyShiftMax);
-                float f;
-                if (__builtin_amdgcn_ballot_w64(lost) != 0)
-                    f = lazy_redo_pack<T, 1>(acc, bfrag, st, risky, c_log2, general, jb, nvis);
-                else if (std::is_same<T, BF16>::value)
-                    f = lazy_shift_inplace_bf16(bfrag, 2, st, risky, spec);
-                else
-                    f = lazy_shift_pack<T, 1>(acc, bfrag, st, risky, spec, c_log2, general, jb, nvis);
-#pragma unroll
-                for (int i = 0; i < NDB; ++i)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) U[i][r] *= f;
-            }
-        } else {
-            float f;
-            if (general) f = online_pack<T, 1, true>(acc, bfrag, lam, beta, c_log2, jb, nvis);
-            else f = online_pack<T, 1, false>(acc, bfrag, lam, beta, c_log2, jb, nvis);
+        auto scale_u = [&](float f) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) U[i][r] *= f;
+        };
+        if (MODE == kTileModeLazy) {
+            bool risky;
+            LazySpec spec;
+            if (general) risky = lazy_spec_pack<T, 1, true, true, TL>(acc, bfrag, st, c_log2, jb, nvis, lane, spec, wary);
+            else risky = lazy_spec_pack<T, 1, false, false, TL>(acc, bfrag, st, c_log2, jb, nvis, lane, spec, wary);
+            if (spec.any_moved) scale_u(spec.fu);
+            if (!spec.checked && __builtin_amdgcn_ballot_w64(risky) != 0) {
+                // rare: bf16 with a sum that is still a number moves the reference by a power
+                // of two in place; everything else takes the checked step on the raw scores
+                const bool lost = risky && !(spec.psum <= kLazyShiftMax);
+                float f;
+                bool moved;
+                if (std::is_same<T, BF16>::value && __builtin_amdgcn_ballot_w64(lost) == 0)
+                    f = lazy_shift_inplace_bf16<TL>(bfrag, 2, st, risky, spec);
+                else if (general)
+                    f = lazy_checked_pack<T, 1, true, TL>(acc, bfrag, st, risky, c_log2, jb, nvis, moved);
+                else
+                    f = lazy_checked_pack<T, 1, false, TL>(acc, bfrag, st, risky, c_log2, jb, nvis, moved);
+                wary.failed();
+                scale_u(f);
+            }
+        } else if (MODE == kTileModeOnline) {
+            float f;
+            if (general) f = online_pack<T, 1, true>(acc, bfrag, lam, beta, c_log2, jb, nvis);
+            else f = online_pack<T, 1, false>(acc, bfrag, lam, beta, c_log2, jb, nvis);
+            if (__builtin_amdgcn_ballot_w64(f != 1.0f) != 0) scale_u(f);
+        } else {
+            float f;
+            if (general) f = blend_pack<T, 1, true>(acc, bfrag, bl, c_log2, jb, nvis);
+            else f = blend_pack<T, 1, false>(acc, bfrag, bl, c_log2, jb, nvis);
+            scale_u(f);
         }
 #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2) {
@@ -243,9 +259,13 @@ void decode_kernel(Problem p) {
 
     // ---- fold the four wavefront states (sigmoid rule on runs of keys) --------------
     float fin, lam_out;
-    if (!ONLINE) {
+    if (MODE == kTileModeLazy) {
         fin = st.beta;                     // the state is the output: o = beta U
-        lam_out = st.one == 0.0f ? ninf : st.R - log2_fast(st.beta);
+        lam_out = st.one == 0.0f ? ninf
+                  : kTL ? st.R + log2_fast(st.ltrue) : st.R - log2_fast(st.beta);
+    } else if (MODE == kTileModeBlend) {
+        fin = 1.0f;
+        lam_out = bl.one == 0.0f ? ninf : bl.lam;
     } else {
         row_finish<true>(lam, beta, fin, lam_out);
     }
@@ -296,15 +316,24 @@ void decode_kernel(Problem p) {
 }
 
 template <typename T, int D>
-static hipError_t launch_decode_t(const Problem& p, bool online, hipStream_t st) {
+static hipError_t launch_decode_t(const Problem& p, int mode, hipStream_t st) {
     dim3 grid((unsigned)p.splits, (unsigned)p.Hkv, (unsigned)p.B);
+    const dim3 block(kDecThreads);
+    // the true log-sum-exp is wanted wherever the state leaves the kernel
+    const bool tl = p.partial != 0;
     if (p.kv8) {
-        if (online) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((decode_kernel<T, D, false, true>), grid, dim3(kDecThreads), 0, st, p);
-    } else if (online) {
-        hipLaunchKernelGGL((decode_kernel<T, D, true, false>), grid, dim3(kDecThreads), 0, st, p);
+        if (mode != kTileModeLazy) return hipErrorInvalidValue;
+        if (tl) hipLaunchKernelGGL((decode_kernel<T, D, kTileModeLazy, true, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((decode_kernel<T, D, kTileModeLazy, true, false>), grid, block, 0, st, p);
+    } else if (mode == kTileModeOnline) {
+        hipLaunchKernelGGL((decode_kernel<T, D, kTileModeOnline, false, false>), grid, block, 0, st, p);
+    } else if (mode == kTileModeBlend) {
+        hipLaunchKernelGGL((decode_kernel<T, D, kTileModeBlend, false, false>), grid, block, 0, st, p);
+    } else if (mode == kTileModeLazy) {
+        if (tl) hipLaunchKernelGGL((decode_kernel<T, D, kTileModeLazy, false, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((decode_kernel<T, D, kTileModeLazy, false, false>), grid, block, 0, st, p);
     } else {
-        hipLaunchKernelGGL((decode_kernel<T, D, false, false>), grid, dim3(kDecThreads), 0, st, p);
+        return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !p.merge) return e;
@@ -317,12 +346,12 @@ bool decode_applies(int Hq, int Hkv, int Lq) {
 
 long decode_workgroups(int B, int Hkv) { return (long)B * Hkv; }
 
-hipError_t launch_decode(const Problem& p, bool online, hipStream_t st) {
+hipError_t launch_decode(const Problem& p, int mode, hipStream_t st) {
     if (!decode_applies(p.Hq, p.Hkv, p.Lq)) return hipErrorInvalidValue;
-    if (p.dtype == 1 && p.d == 64) return launch_decode_t<F16, 64>(p, online, st);
-    if (p.dtype == 1 && p.d == 128) return launch_decode_t<F16, 128>(p, online, st);
-    if (p.dtype == 2 && p.d == 64) return launch_decode_t<BF16, 64>(p, online, st);
-    if (p.dtype == 2 && p.d == 128) return launch_decode_t<BF16, 128>(p, online, st);
+    if (p.dtype == 1 && p.d == 64) return launch_decode_t<F16, 64>(p, mode, st);
+    if (p.dtype == 1 && p.d == 128) return launch_decode_t<F16, 128>(p, mode, st);
+    if (p.dtype == 2 && p.d == 64) return launch_decode_t<BF16, 64>(p, mode, st);
+    if (p.dtype == 2 && p.d == 128) return launch_decode_t<BF16, 128>(p, mode, st);
     return hipErrorInvalidValue;
 }
 

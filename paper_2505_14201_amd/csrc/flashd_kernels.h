@@ -14,16 +14,20 @@ hipError_t launch_perkey(const Problem& p, hipStream_t st);
 // Fold p.splits partial states per query row from p.ws into p.o.
 hipError_t launch_merge_splits(const Problem& p, hipStream_t st);
 
-// Alg. 3 on key tiles (matrix cores, f16/bf16); online = the Alg. 2 ablation.
-// With p.splits > 1 also folds the partials.
-hipError_t launch_tile(const Problem& p, bool online, hipStream_t st);
+// How a tile of keys updates a row in the matrix-core kernels: 0 = Alg. 3 with the blend
+// factor deferred (variant TILE), 1 = the Alg. 2 ablation, 2 = Alg. 3 with the blend applied
+// on every tile (variant TILE_BLEND).
+constexpr int kTileModeLazy = 0, kTileModeOnline = 1, kTileModeBlend = 2;
+
+// Alg. 3 on key tiles (matrix cores, f16/bf16).  With p.splits > 1 also folds the partials.
+hipError_t launch_tile(const Problem& p, int mode, hipStream_t st);
 
 // Number of workgroups launch_tile uses per split.
 long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d);
 
 // Split-K decode on the matrix cores for (Hq / Hkv) * Lq <= 32 query rows per kv head
-// (f16/bf16); online = the Alg. 2 ablation.  With p.splits > 1 also folds the partials.
-hipError_t launch_decode(const Problem& p, bool online, hipStream_t st);
+// (f16/bf16); mode as for launch_tile.  With p.splits > 1 also folds the partials.
+hipError_t launch_decode(const Problem& p, int mode, hipStream_t st);
 bool decode_applies(int Hq, int Hkv, int Lq);
 long decode_workgroups(int B, int Hkv);
 

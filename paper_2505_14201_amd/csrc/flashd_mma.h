@@ -130,30 +130,41 @@ __device__ __forceinline__ u32x4 lds_read_v_operand(const uint16_t* base, int ro
 }
 
 // ---------------------------------------------------------------------------
-// The tile rule of Alg. 3 with the blend factor kept as a scalar ("lazy blend"), used by the
-// prefill and the decode kernel.  After a run of keys the state of Alg. 3 is
-// (o, s_last, ln w_last) and only Lam = s_last - ln w_last enters later steps; a tile of keys
-// acts as one key.  A row's state here is (U, R, beta, one):
+// The tile rule of Alg. 3 as the matrix-core kernels apply it by default ("lazy blend"; the
+// literal per-tile blend is blend_pack() further down).  After a run of keys the state of
+// Alg. 3 is (o, s_last, ln w_last) and only Lam = s_last - ln w_last enters later steps; a tile
+// of keys acts as one key.  A row's state here is (U, R, beta, one):
 //     true output o = beta U,   Lam = R - log2 beta,   one = 0 until the row has seen a key.
 // For a tile, with p_j = 2^{s_j - R} (R does not move on this path) and psum = sum_j p_j,
 //     tot = one + beta psum,   1 - W = 1/tot   (W = sigmoid(S_tile - Lam), the tile's weight),
 //     U <- U + sum_j p_j v_j,  beta <- beta (1 - W).
 // This is o <- (1 - W)(o + sum_j 2^{s_j - Lam} v_j) with the vector multiplication by
-// (1 - W) folded into the scalar beta: U is never rescaled here.  An empty row takes the
-// score of the tile's first key as R (w_1 = 1 for that key).
+// (1 - W) folded into the scalar beta: U is never rescaled here.  Said the other way round:
+// 1/beta is the sum of 2^{s_j - R} over the keys seen so far, taken against a reference R that
+// is not a running maximum and does not move unless it has to, and o = beta U at the store is
+// the normalisation by that sum, applied once.  An empty row takes the score of the tile's
+// first key as R (w_1 = 1 for that key).
 //
 // lazy_spec_pack() does that speculatively, branch-free, leaving the raw scores untouched,
 // and reports rows whose psum left the safe range (some 2^{s_j - R} too large for the
-// storage type: a score far above everything before it).  If that psum is still an ordinary
-// fp32 number the tile's total is known and only the coefficients do not fit:
-// lazy_shift_pack() moves the row's reference up by a power of two and rounds the
-// coefficients again.  If psum itself overflowed, lazy_redo_pack() redoes the tile from the
-// raw scores with the key-by-key sigmoid recurrence, which saturates instead of overflowing,
-// and moves R.
+// storage type: a score far above everything before it -- the case in which the sigmoid of
+// the weight equation saturates at 1, Sec. III-C).  For bf16, whose coefficients have the
+// range of fp32, a psum that is still an ordinary number is served by
+// lazy_shift_inplace_bf16(): the reference moves up by a power of two and the coefficients are
+// scaled as they are.  Everything else goes through lazy_checked_pack(): the row's top score
+// of the tile is looked at BEFORE anything is exponentiated, and a row whose top score lies
+// far above its reference takes that score as its new reference (the saturating key takes
+// the weight to 1 and everything before it is scaled down by 2^{R - R'}, which underflows to
+// zero where the sigmoid would).  A wavefront that has needed the checked step keeps using it
+// (instead of speculating and forming the tile's scores a second time) until a run of tiles
+// has left every reference where it was.
 struct LazyRow {
     float R;      // exponent reference, log2 units
     float beta;   // o = beta * U
     float one;    // 0.0f while the row is empty, then 1.0f
+    float ltrue;  // only where the coefficient sums are those of the rounded coefficients and
+                  // the state is handed out: the sum of the unrounded 2^{s_j - R}, so that
+                  // Lam = R + log2 ltrue is the true log-sum-exp
 };
 
 // What the speculative pass found for a row: the sum of its coefficients and the reference
@@ -161,6 +172,11 @@ struct LazyRow {
 struct LazySpec {
     float psum;
     float ref;
+    float ptrue;  // sum of the unrounded coefficients (see LazyRow::ltrue)
+    float fu;     // factor that what the row holds (U) still has to be scaled by; 1 as a rule
+    bool any_moved;   // wavefront-uniform: some row's fu is not 1
+    bool checked;     // wavefront-uniform: the top scores were looked at first, so no row can be
+                      // risky (short of a sum that is not a number)
 };
 
 // psum above this is treated as overflowed.  Below it one + beta psum (beta <= 2) stays far
@@ -169,14 +185,27 @@ struct LazySpec {
 constexpr float kLazyShiftMax = 1.0e30f;      // ~2^100
 
 template <typename T> struct LazyLimit;
-template <> struct LazyLimit<BF16> { static constexpr float kMaxPsum = 1.0e18f; };   // ~2^60
-template <> struct LazyLimit<F16> { static constexpr float kMaxPsum = 16384.0f; };   // each p_j < 2^14
+// kMaxPsum: the speculative pass trusts a tile whose coefficient sum stays below this.
+// kMoveLog2: the checked step moves a row's reference once a score lies this far above it.
+template <> struct LazyLimit<BF16> {
+    static constexpr float kMaxPsum = 1.0e18f;       // ~2^60
+    static constexpr float kMoveLog2 = 54.0f;
+};
+template <> struct LazyLimit<F16> {
+    static constexpr float kMaxPsum = 16384.0f;      // each p_j < 2^14
+    static constexpr float kMoveLog2 = 13.0f;
+};
 
 // x[lane] + x[lane ^ 32] without touching LDS: the swap returns {x_lo, x_lo} and {x_hi, x_hi}
 __device__ __forceinline__ float pair_sum(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x),
                                                     false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float pair_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x),
+                                                    false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 // the value held by the hh = 0 lane of the pair
 __device__ __forceinline__ float pair_low(float x) {
@@ -185,21 +214,85 @@ __device__ __forceinline__ float pair_low(float x) {
     return __uint_as_float(r[0]);
 }
 
+// The largest scaled score (log2 units) of the lane pair's row over NB 32-key blocks; -inf
+// if every key is masked.  Without a mask the raw dot products are compared and the result
+// scaled once (a negative scale turns the order round).
+template <int NB, bool MASK>
+__device__ __forceinline__ float row_top_score(const f32x16 (&acc)[NB], float c_log2, int jb,
+                                               int nvis) {
+    const float ninf = -__builtin_inff();
+    float m;
+    if (!MASK) {
+        if (c_log2 >= 0.0f) {
+            m = acc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[kb][r]);
+        } else {
+            m = acc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = fminf(m, acc[kb][r]);
+        }
+        m *= c_log2;
+    } else {
+        m = ninf;
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float x = acc[kb][r] * c_log2;
+                m = fmaxf(m, ((jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) ? ninf : x);
+            }
+    }
+    return pair_max(m);
+}
+
 // acc: raw dot products of NB 32-key blocks in the accumulator layout (not modified).
 // bfrag[g]: the coefficients of 16-key group g, rounded to the storage type, as the B
 // operand of the output product.  jb = index of the key in register 0 of block 0 for this
 // lane (tile start + 4 hh).  MASK = false: every key is visible to every row of the
 // wavefront.  Returns true if the row is risky; its state is then left untouched.
 // MAY_BE_EMPTY = false promises that no row of the wavefront is still empty (true from a
-// row's second unit on); the code is then free of the first-key logic and stays one
-// basic block, which the caller needs to interleave it with matrix instructions.
-template <typename T, int NB, bool MASK, bool MAY_BE_EMPTY>
+// row's second unit on); the code is then free of the first-key logic.
+// TL: also carry the sum of the unrounded coefficients (LazyRow::ltrue).
+// wary (wavefront-uniform) > 0: the wavefront has lately needed the checked step, so the
+// rows' top scores are looked at before the exponentials (a few instructions, against a
+// failed speculation that costs the tile's scores and exponentials a second time): a row
+// whose top score lies more than LazyLimit::kMoveLog2 above its reference takes that score as
+// its reference, what it holds is scaled by f = 2^{R - R'} (left to the caller: spec.fu,
+// 1 for rows that stay, and spec.any_moved for the wavefront), and at least kWaryTiles more
+// tiles are looked at; a tile that moves no reference counts wary.left down.  Every failed
+// speculation multiplies the number of tiles the wavefront then stays wary for (wary.len) by
+// 16: inputs whose scores keep jumping soon look at every tile (a failed speculation costs
+// about one more tile, the look a percent of one), inputs of ordinary range never start.
+// (Looking at every row's first tile as a matter of course was measured and lost 3-8 %: with
+// the mask in play the look costs three instructions per score.)
+constexpr int kWaryTiles = 64;
+struct Wary {
+    int left;     // > 0: look at the top scores before exponentiating
+    int len;      // tiles to stay wary for after the next failed speculation
+    __device__ __forceinline__ void failed() {
+        left = len;
+        len = len < (1 << 24) ? 16 * len : len;
+    }
+};
+
+template <typename T, int NB, bool MASK, bool MAY_BE_EMPTY, bool TL>
 __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
                                                LazyRow& st, float c_log2, int jb, int nvis,
-                                               int lane, LazySpec& spec) {
+                                               int lane, LazySpec& spec, Wary& wary) {
+    constexpr bool kTL = TL && Mma<T>::kRoundedSum;
     const float ninf = -__builtin_inff();
     bool empty = false;
     float ref = st.R;
+    float fu = 1.0f;          // what the row holds (U, the carried sum) shrinks by this
+    spec.any_moved = false;
+    // a tile whose top scores have been looked at cannot hold a coefficient the storage type
+    // does not: only a sum that is no number at all (NaN input) is then refused
+    const float limit = (wary.left > 0) ? kLazyShiftMax : LazyLimit<T>::kMaxPsum;
     if (MAY_BE_EMPTY) {
         empty = st.one == 0.0f;
         // first key of the tile for this row: register 0 of block 0 in the hh = 0 lane
@@ -207,7 +300,22 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
         const float ref0 = ((jb - 4 * (lane >> 5)) < nvis) ? s0 : 0.0f;
         ref = empty ? ref0 : st.R;
     }
+    spec.checked = wary.left > 0;
+    if (spec.checked) {
+        // branch-free apart from the wavefront-uniform test above: the few instructions
+        // below cost less than waiting for a vector compare to reach a scalar branch
+        const float m = row_top_score<NB, MASK>(acc, c_log2, jb, nvis);
+        const bool move = !empty && (m - st.R > LazyLimit<T>::kMoveLog2);
+        // an empty row starts from its top score rather than its first: no coefficient above 1
+        if (MAY_BE_EMPTY) ref = (empty && m != ninf) ? m : ref;
+        fu = move ? exp2_fast(st.R - m) : 1.0f;
+        ref = move ? m : ref;
+        spec.any_moved = __builtin_amdgcn_ballot_w64(move) != 0;
+        wary.left = spec.any_moved ? (wary.left < kWaryTiles ? kWaryTiles : wary.left)
+                                   : (wary.left > 0 ? wary.left - 1 : 0);
+    }
     f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float pt0 = 0.0f, pt1 = 0.0f;
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -220,6 +328,10 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
         }
         bfrag[g] = Mma<T>::pack8(pv);
         Mma<T>::sum8(pv, bfrag[g], ps4);
+        if (kTL) {
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) { pt0 += pv[e]; pt1 += pv[e + 1]; }
+        }
         // Keep the groups apart: scheduled together, the 32 exponents and 32 results of a
         // tile are all live at once, and the register allocator then starts to move the
         // accumulators around.  Eight independent elements are enough to hide latencies.
@@ -228,72 +340,39 @@ __device__ __forceinline__ bool lazy_spec_pack(const f32x16 (&acc)[NB], u32x4 (&
     float psum = pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
     spec.psum = psum;
     spec.ref = ref;
-    const bool safe = psum <= LazyLimit<T>::kMaxPsum;             // false for inf and NaN
+    spec.ptrue = kTL ? pair_sum(pt0 + pt1) : 0.0f;
+    spec.fu = fu;
+    const bool safe = psum <= limit;             // false for inf and NaN
+    // 1/beta is the carried sum: beta' = 1 / (fu / beta + psum) = beta / (fu + beta psum)
     if (MAY_BE_EMPTY) {
         const bool upd = safe & !(empty & (psum == 0.0f));
-        const float tot = fmaf(st.beta, psum, st.one);
+        const float tot = fmaf(st.beta, psum, st.one * fu);
         const float nb = st.beta * __builtin_amdgcn_rcpf(tot);
         st.beta = upd ? nb : st.beta;
         st.R = upd ? ref : st.R;
         st.one = upd ? 1.0f : st.one;
+        if (kTL) st.ltrue = upd ? fmaf(fu, st.ltrue, spec.ptrue) : st.ltrue;
     } else {
-        const float nb = st.beta * __builtin_amdgcn_rcpf(fmaf(st.beta, psum, 1.0f));
+        const float nb = st.beta * __builtin_amdgcn_rcpf(fmaf(st.beta, psum, fu));
         st.beta = safe ? nb : st.beta;
+        st.R = safe ? ref : st.R;
+        if (kTL) st.ltrue = safe ? fmaf(fu, st.ltrue, spec.ptrue) : st.ltrue;
     }
     return !safe;
 }
 
-// Middle path, entered by the whole wavefront when some row is risky and every risky row's
-// psum is an ordinary number.  For a risky row the update of the state is the one of the
-// common path (tot = one + beta psum); its reference moves up by e = exponent of psum
-// (psum = m 2^e, 1/2 <= m < 1), so that every coefficient 2^{s_j - R - e} <= m < 1 fits the
-// storage type; what the row holds shrinks with it, U by 2^-e (the returned factor) and beta
-// by 2^e the other way, o = beta U unchanged.  The other rows' coefficients are formed again
-// with the reference they used (same values).  No maximum is taken and no key is looked at
-// on its own.
-template <typename T, int NB>
-__device__ __forceinline__ float lazy_shift_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
-                                                 LazyRow& st, bool risky, const LazySpec& spec,
-                                                 float c_log2, bool need_mask, int jb, int nvis) {
-    const float ninf = -__builtin_inff();
-    float f = 1.0f;
-    float ref = st.R;     // rows that were not risky: the reference lazy_spec_pack used
-    if (risky) {
-        const int e = __builtin_amdgcn_frexp_expf(spec.psum);
-        const bool empty = st.one == 0.0f;
-        const float tot = fmaf(st.beta, spec.psum, st.one);
-        const float nb = st.beta * __builtin_amdgcn_rcpf(tot);       // below 2^-e, then scaled up
-        st.beta = __builtin_ldexpf(nb, e);
-        ref = spec.ref + (float)e;
-        st.R = ref;
-        st.one = 1.0f;
-        f = empty ? 0.0f : __builtin_ldexpf(1.0f, -e);
-    }
-    int nv = nvis;
-    asm volatile("" : "+v"(nv));      // see lazy_redo_pack
-#pragma unroll
-    for (int g = 0; g < 2 * NB; ++g) {
-        f32x8 pv;
-#pragma unroll
-        for (int e8 = 0; e8 < 8; ++e8) {
-            const int r = 8 * (g & 1) + e8;
-            float x = fmaf(acc[g >> 1][r], c_log2, -ref);
-            const bool masked = need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv;
-            if (masked) x = ninf;
-            pv[e8] = exp2_fast(x);
-        }
-        bfrag[g] = Mma<T>::pack8(pv);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    return f;
-}
-
-// The same middle path where the coefficients of the speculative pass are still at hand and
-// have the range of fp32 (bf16): they are not formed again but scaled by 2^-e as they are,
-// by taking e off the exponent field of each (two per instruction, saturating at zero), so
-// that the coefficients the output product uses are bit for bit the ones whose sum went into
-// the state (formed again at the new reference, one that sat on a rounding boundary could
-// land on the other side).  Needs neither the raw scores nor an exponential.
+// Entered by the whole wavefront when some row is risky and every risky row's psum is an
+// ordinary number, for a storage type whose coefficients have the range of fp32 (bf16): the
+// coefficients of the speculative pass are still at hand and valid.  For a risky row the
+// update of the state is the one of the common path (tot = one + beta psum); its reference
+// moves up by e = exponent of psum (psum = m 2^e, 1/2 <= m < 1); what the row holds shrinks
+// with it, U by 2^-e (the returned factor) and beta by 2^e the other way, o = beta U
+// unchanged.  The coefficients are not formed again but scaled by 2^-e as they are, by taking
+// e off the exponent field of each (two per instruction, saturating at zero), so that the
+// coefficients the output product uses are bit for bit the ones whose sum went into the
+// state (formed again at the new reference, one that sat on a rounding boundary could land
+// on the other side).  Needs neither the raw scores nor an exponential, and no maximum.
+template <bool TL>
 __device__ __forceinline__ float lazy_shift_inplace_bf16(u32x4* bfrag, int ngroups, LazyRow& st,
                                                          bool risky, const LazySpec& spec) {
     typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
@@ -307,6 +386,7 @@ __device__ __forceinline__ float lazy_shift_inplace_bf16(u32x4* bfrag, int ngrou
         st.beta = __builtin_ldexpf(nb, e);
         st.R = spec.ref + (float)e;
         st.one = 1.0f;
+        if (TL) st.ltrue = __builtin_ldexpf(st.ltrue + spec.ptrue, -e);
         f = empty ? 0.0f : __builtin_ldexpf(1.0f, -e);
         sub = (unsigned)e << 7;          // 0 < e <= 100: fits the field
     }
@@ -324,51 +404,38 @@ __device__ __forceinline__ float lazy_shift_inplace_bf16(u32x4* bfrag, int ngrou
     return f;
 }
 
-// Rare path, entered by the whole wavefront when any of its rows is risky.  Key-by-key
-// recurrence inside the lane over the raw scores: Lam_j = Lam_{j-1} + softplus(s_j -
-// Lam_{j-1}), i.e. w_j = sigmoid(s_j - s_{j-1} + ln w_{j-1}) carried as Lam = s - ln w; the
-// first visible key starts the run (w = 1); the lane pair and the carried state are folded
-// by the same rule.  Risky rows get c_j = 2^{s_j - Lam_new} <= 1 and a new reference; the
-// other rows' coefficients are recomputed with the reference they used (same values; a
-// row that is still empty has every key masked, so its reference does not matter).
-// Returns the factor for the row's U (1 for rows that were not risky).
-template <typename T, int NB>
-__device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
-                                                LazyRow& st, bool risky, float c_log2,
-                                                bool need_mask, int jb, int nvis) {
+// The checked step.  Rows with update = true have not had this tile applied to their state
+// yet; the others have (by lazy_spec_pack) and only get their coefficients formed again with
+// the reference they used (same values).  For a row to update, the tile's top score m is
+// compared with the reference first.  If m lies more than LazyLimit::kMoveLog2 above R (or
+// the row is still empty) the reference moves to m: every coefficient is then 2^{s_j - m} <= 1,
+// what the row holds is scaled by f = 2^{R - m} (the returned factor, for U; 1/beta, the
+// carried sum, likewise), and a jump too large for fp32 simply makes f zero: the earlier keys'
+// weight has saturated at 0 as the sigmoid's would (Sec. III-C).  Otherwise the reference
+// stays and the coefficients are at most 2^kMoveLog2, which the storage type holds.  The sum
+// can no longer overflow, so this step has no fallback of its own.  `moved` tells the caller
+// whether this lane's U needs the factor.
+template <typename T, int NB, bool MASK, bool TL>
+__device__ __forceinline__ float lazy_checked_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                                   LazyRow& st, bool update, float c_log2, int jb,
+                                                   int nvis, bool& moved) {
+    constexpr bool kTL = TL && Mma<T>::kRoundedSum;
     const float ninf = -__builtin_inff();
-    // The mask compares are redone here from values the compiler cannot connect with the
-    // ones of lazy_spec_pack (empty asm); shared, 32 compare results would stay live
-    // across the branch into this rare path.
-    int nv1 = nvis, nv2 = nvis;
-    asm volatile("" : "+v"(nv1));
-    float ll = ninf;
-#pragma unroll
-    for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const bool masked = need_mask && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nv1;
-            ll = lse2(ll, masked ? ninf : acc[kb][r] * c_log2);
-            // rare path: keep it sequential so that it does not add to the register need
-            if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-        }
-    ll = lse2(ll, __shfl_xor(ll, 32, 64));                  // partner lane's run
+    const float m = row_top_score<NB, MASK>(acc, c_log2, jb, nvis);
     const bool empty = st.one == 0.0f;
-    const float lam_old = empty ? ninf : st.R - log2_fast(st.beta);
-    const float lam_new = lse2(lam_old, ll);                  // the tile acts as one key
-    const bool none = risky && lam_new == ninf;
-    float f = 1.0f;
-    float ref = st.R;     // rows that were not risky: the reference lazy_spec_pack used
-    float w_old = 0.0f;   // 1 - W = 2^{Lam_old - Lam_new}: what is left of the old state
-    if (risky) {
-        ref = none ? 0.0f : lam_new;
-        w_old = empty ? 0.0f : exp2_fast(lam_old - lam_new);
-        f = st.beta * w_old;            // applied to U now
-        st.R = ref;
-        st.one = none ? 0.0f : 1.0f;
+    float ref = st.R, f = 1.0f;
+    moved = false;
+    if (update) {
+        const float mref = (m == ninf) ? 0.0f : m;
+        const bool move = empty || (m - st.R > LazyLimit<T>::kMoveLog2);
+        ref = move ? mref : st.R;
+        f = empty ? 0.0f : (move ? exp2_fast(st.R - mref) : 1.0f);
+        moved = move && !empty;
     }
-    asm volatile("" : "+v"(nv2));
+    int nv = nvis;
+    asm volatile("" : "+v"(nv));      // keep these compares apart from row_top_score's
     f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float pt0 = 0.0f, pt1 = 0.0f;
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
         f32x8 pv;
@@ -376,49 +443,46 @@ __device__ __forceinline__ float lazy_redo_pack(const f32x16 (&acc)[NB], u32x4 (
         for (int e = 0; e < 8; ++e) {
             const int r = 8 * (g & 1) + e;
             float x = fmaf(acc[g >> 1][r], c_log2, -ref);
-            const bool masked =
-                need_mask && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv2;
-            if (masked || none) x = ninf;
+            if (MASK) x = ((jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv) ? ninf : x;
             pv[e] = exp2_fast(x);
         }
         bfrag[g] = Mma<T>::pack8(pv);
-        if (Mma<T>::kRoundedSum) Mma<T>::sum8(pv, bfrag[g], ps4);
+        Mma<T>::sum8(pv, bfrag[g], ps4);
+        if (kTL) {
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) { pt0 += pv[e]; pt1 += pv[e + 1]; }
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
-    if (risky) {
-        // Exactly, w_old and the tile's coefficients sum to one and beta is 1.  Where the row
-        // sums are those of the rounded coefficients (Mma::sum8) beta takes the sum they
-        // really have, so that o = beta U stays a weighted mean of the values.
-        float tot = 1.0f;
-        if (Mma<T>::kRoundedSum) tot = w_old + pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
-        st.beta = (none || !Mma<T>::kRoundedSum) ? 1.0f : __builtin_amdgcn_rcpf(tot);
+    const float psum = pair_sum((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
+    const float ptrue = kTL ? pair_sum(pt0 + pt1) : 0.0f;
+    if (update) {
+        // 1/beta is the carried sum; against the new reference it shrinks by f
+        const float carried = empty ? 0.0f : f * __builtin_amdgcn_rcpf(st.beta);
+        const float tot = carried + psum;
+        const bool has = tot > 0.0f;        // false only for an empty row that sees no key here
+        st.beta = has ? __builtin_amdgcn_rcpf(tot) : st.beta;
+        st.R = has ? ref : st.R;
+        st.one = has ? 1.0f : st.one;
+        if (kTL) st.ltrue = has ? fmaf(f, st.ltrue, ptrue) : st.ltrue;
     }
     return f;
 }
 
 // Alg. 2 on the same interface (ablation): m_i = max(m_{i-1}, s), l_i = l_{i-1}
-// e^{m_{i-1}-m_i} + sum e^{s-m_i}; returns the factor e^{m_{i-1}-m_i} for the row's U.
+// e^{m_{i-1}-m_i} + sum e^{s-m_i}; returns the factor e^{m_{i-1}-m_i} for the row's U, which
+// is exactly 1 unless the maximum has moved (the caller skips the scaling of U while no row of
+// the wavefront has a new maximum).
 template <typename T, int NB, bool MASK>
 __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
                                              float& m, float& l, float c_log2, int jb, int nvis) {
     const float ninf = -__builtin_inff();
-    float mx = ninf;
-#pragma unroll
-    for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float s = acc[kb][r] * c_log2;
-            if (MASK && (jb + 32 * kb + 8 * (r >> 2) + (r & 3)) >= nvis) s = ninf;
-            mx = fmaxf(mx, s);
-        }
-    {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx),
-                                                         false, false);
-        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
+    const float mx = row_top_score<NB, MASK>(acc, c_log2, jb, nvis);
     const float m_new = fmaxf(m, mx);
     const float m_use = (m_new == ninf) ? 0.0f : m_new;
     const float resc = exp2_fast(m - m_use);
+    int nv = nvis;
+    asm volatile("" : "+v"(nv));
     f32x4 ps4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int g = 0; g < 2 * NB; ++g) {
@@ -427,7 +491,7 @@ __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bf
         for (int e = 0; e < 8; ++e) {
             const int r = 8 * (g & 1) + e;
             float x = fmaf(acc[g >> 1][r], c_log2, -m_use);
-            if (MASK && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nvis) x = ninf;
+            if (MASK && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv) x = ninf;
             pv[e] = exp2_fast(x);
         }
         bfrag[g] = Mma<T>::pack8(pv);
@@ -438,6 +502,77 @@ __device__ __forceinline__ float online_pack(const f32x16 (&acc)[NB], u32x4 (&bf
     l = l * resc + psum;
     m = m_new;
     return resc;
+}
+
+// The blend of Sec. III-A applied literally per tile (variant TILE_BLEND): the row holds the
+// output o itself (in U) and Lam; a tile of keys acts as one key of score
+// Lam_tile = log2 sum_j 2^{s_j} and value o_tile = sum_j 2^{s_j - Lam_tile} v_j, its weight is
+// W = sigmoid(Lam_tile - Lam) (weight equation of Sec. III-B on the run states), and
+//     o <- (1 - W) o + W o_tile = (1 - W) o + sum_j c_j v_j,   c_j = 2^{s_j - Lam_new} <= 1,
+//     Lam_new = Lam - log2(1 - W).
+// Nothing is deferred: U is scaled by (1 - W) on every tile and the coefficients are final
+// weights, so the stored row is U as it stands.  The sigmoid is evaluated from its saturating
+// side, i.e. the exponentials are taken against ref = the larger of Lam and the tile's top
+// score, where all of them are <= 1:  a = 2^{Lam - ref}, p_j = 2^{s_j - ref}, tot = a + sum p_j,
+// 1 - W = a / tot, c_j = p_j / tot, Lam_new = ref + log2 tot.  No overflow is possible and
+// there is no fallback path.  Where the coefficient sums are those of the rounded
+// coefficients (bf16), 1 - W is taken as 1 - sum of the rounded c_j, so that the row stays a
+// weighted mean of the values.  Returns 1 - W (the factor for U).
+struct BlendRow {
+    float lam;    // log2 units; meaningless while one == 0
+    float one;    // 0.0f while the row is empty, then 1.0f
+};
+
+template <typename T, int NB, bool MASK>
+__device__ __forceinline__ float blend_pack(const f32x16 (&acc)[NB], u32x4 (&bfrag)[2 * NB],
+                                            BlendRow& st, float c_log2, int jb, int nvis) {
+    const float ninf = -__builtin_inff();
+    const float m = row_top_score<NB, MASK>(acc, c_log2, jb, nvis);
+    const bool empty = st.one == 0.0f;
+    const float mref = (m == ninf) ? 0.0f : m;
+    const float ref = empty ? mref : fmaxf(st.lam, m);
+    const float a = empty ? 0.0f : exp2_fast(st.lam - ref);
+    int nv = nvis;
+    asm volatile("" : "+v"(nv));
+    f32x8 pv[2 * NB];
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = 8 * (g & 1) + e;
+            float x = fmaf(acc[g >> 1][r], c_log2, -ref);
+            if (MASK && (jb + 32 * (g >> 1) + 8 * (r >> 2) + (r & 3)) >= nv) x = ninf;
+            pv[g][e] = exp2_fast(x);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; e += 4) {
+            s0 += pv[g][e]; s1 += pv[g][e + 1]; s2 += pv[g][e + 2]; s3 += pv[g][e + 3];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    const float psum = pair_sum((s0 + s1) + (s2 + s3));
+    const float tot = a + psum;
+    const bool has = tot > 0.0f;            // false only for an empty row that sees no key here
+    const float cs = has ? __builtin_amdgcn_rcpf(tot) : 0.0f;
+    f32x4 cs4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < 2 * NB; ++g) {
+        f32x8 cv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cv[e] = pv[g][e] * cs;
+        bfrag[g] = Mma<T>::pack8(cv);
+        if (Mma<T>::kRoundedSum) Mma<T>::sum8(cv, bfrag[g], cs4);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float omw = a * cs;                      // 1 - W = sigmoid(Lam - Lam_tile)
+    if (Mma<T>::kRoundedSum) {
+        const float csum = pair_sum((cs4[0] + cs4[1]) + (cs4[2] + cs4[3]));
+        omw = fmaxf(1.0f - csum, 0.0f);
+    }
+    st.lam = has ? ref + log2_fast(tot) : st.lam;
+    st.one = has ? 1.0f : st.one;
+    return empty ? 0.0f : omw;
 }
 
 // What a finished row hands on: the factor that turns U into the output, and the row's

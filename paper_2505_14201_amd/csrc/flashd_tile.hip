@@ -1,5 +1,5 @@
-// Alg. 3 lifted to key tiles on the gfx950 matrix cores (variant TILE), and the
-// Alg. 2 ablation (running max, running sum, final division) on the same tiling
+// Alg. 3 lifted to key tiles on the gfx950 matrix cores (variants TILE and TILE_BLEND), and
+// the Alg. 2 ablation (running max, running sum, final division) on the same tiling
 // (variant ONLINE_SOFTMAX).  Storage types f16 and bf16, fp32 state and accumulation.
 //
 // Tile form of the recurrence.  The state of Alg. 3 after a run of keys is
@@ -9,12 +9,17 @@
 //     1 - W = 1/tot   (W = sigmoid(S_tile - Lam) is the tile's weight),
 //     o <- (1 - W) (o + sum_j p_j v_j),      Lam <- Lam + ln tot,
 // which is the blend o <- (1 - W) o + W o_tile of Sec. III-A with the tile's own
-// weighted value o_tile = sum_j p_j v_j / sum_j p_j.  No maximum is tracked and the
-// output is not divided by a running sum of exponentials.  The product of the (1 - W)
-// factors is carried as one scalar per row and multiplied in when the row is stored
-// (flashd_mma.h, "lazy blend").  A score far above everything before it would overflow
-// e^{s_j - Lam}; such rows redo the tile with the key-by-key sigmoid recurrence, which
-// saturates instead (Sec. III-C).
+// weighted value o_tile = sum_j p_j v_j / sum_j p_j.
+//   TILE_BLEND applies exactly that on every tile: U holds o, is scaled by (1 - W) per tile,
+// and the coefficients are the final weights c_j = e^{s_j - Lam_new} <= 1 (blend_pack).
+//   TILE, the default, defers the scaling: the product of the (1 - W) factors is carried as
+// one scalar beta per row and multiplied in when the row is stored, and the coefficients are
+// taken against a reference R that only moves when it has to (flashd_mma.h, "lazy blend").
+// In that form 1/beta IS a sum of exponentials 2^{s_j - R} over the keys seen so far and
+// o = beta U at the store is the normalisation by it: what TILE does without, compared with
+// Alg. 2, is the running maximum and the per-tile rescaling of the accumulator, not the sum.
+// A score far above everything before it would overflow e^{s_j - R}; the row's reference then
+// moves to that score, which is the saturation of the sigmoid at 1 (Sec. III-C) in tile form.
 //
 // Mapping.  A workgroup of 4 wavefronts owns 128 query rows of one (b, h); a wavefront
 // owns 32 of them.  Keys stream through LDS in tiles of 64, double-buffered: the next
@@ -40,6 +45,11 @@
 namespace flashd {
 
 constexpr int kBC = 64;           // keys per tile
+
+// How a tile's scores update a row (the kernel's MODE argument)
+constexpr int kModeLazy = kTileModeLazy;        // variant TILE
+constexpr int kModeOnline = kTileModeOnline;    // variant ONLINE_SOFTMAX (Alg. 2)
+constexpr int kModeBlend = kTileModeBlend;      // variant TILE_BLEND
 
 // LDS layout of one K or V tile: [64 keys][D] elements, rows unpadded (the direct
 // global->LDS loads write 64 consecutive 16-byte chunks per instruction, so rows cannot
@@ -172,7 +182,8 @@ template <int D> struct TileRegs {
     int kaddr[D / 16];
     int vaddr[D / 32];
     f32x16 U[D / 32];
-    LazyRow st;             // FLASH-D state
+    LazyRow st;             // FLASH-D state, lazy form
+    BlendRow bl;            // FLASH-D state, literal per-tile blend
     float lam, beta;        // Alg. 2 state: running max m, running sum l
 };
 
@@ -214,55 +225,67 @@ __device__ __forceinline__ void phase_scores(const uint16_t* ks, const TileRegs<
 // the variant needs it, the scaling of U.  general = false promises that every key of the
 // tile is visible to every row of the wavefront and that no row is still empty (not the
 // first tile of a row); the common code path then carries neither the mask nor the
-// first-key logic.
-template <typename T, int D, bool ONLINE>
+// first-key logic.  wary (wavefront-uniform): see lazy_spec_pack.
+template <typename T, int D, int MODE, bool TL>
 __device__ __forceinline__ void phase_coeffs(const uint16_t* ks, const f32x16 (&acc)[2],
                                              u32x4 (&bfrag)[4], TileRegs<D>& g, int j0, int hh,
-                                             int lane, int nvis, bool general, float c_log2) {
+                                             int lane, int nvis, bool general, float c_log2,
+                                             Wary& wary) {
     constexpr int NDB = D / 32;
     const int jb = j0 + 4 * hh;
-    if (!ONLINE) {
-        bool risky;
-        LazySpec spec;
-        if (general)
-            risky = lazy_spec_pack<T, 2, true, true>(acc, bfrag, g.st, c_log2, jb, nvis, lane,
-                                                     spec);
-        else
-            risky = lazy_spec_pack<T, 2, false, false>(acc, bfrag, g.st, c_log2, jb, nvis, lane,
-                                                       spec);
-        if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-            // rare: a flagged row's coefficients do not fit the storage type.  Its reference
-            // moves up by a power of two (psum still a number), or, where psum itself
-            // overflowed, the rows redo the tile with the key-by-key sigmoid recurrence.  The
-            // raw scores are formed again (K is still in LDS) rather than kept: holding them
-            // until here would cost the common path 32 registers.
-            const bool lost = risky && !(spec.psum <= kLazyShiftMax);
-            const bool any_lost = __builtin_amdgcn_ballot_w64(lost) != 0;
-            float f;
-            if (std::is_same<T, BF16>::value && !any_lost) {
-                f = lazy_shift_inplace_bf16(bfrag, 4, g.st, risky, spec);
-            } else {
-                f32x16 acc2[2];
-                phase_scores<T, D>(ks, g, acc2);
-                if (any_lost)
-                    f = lazy_redo_pack<T, 2>(acc2, bfrag, g.st, risky, c_log2, general, jb, nvis);
-                else
-                    f = lazy_shift_pack<T, 2>(acc2, bfrag, g.st, risky, spec, c_log2, general,
-                                              jb, nvis);
-            }
-#pragma unroll
-            for (int i = 0; i < NDB; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
-        }
-    } else {
-        float f;
-        if (general) f = online_pack<T, 2, true>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
-        else f = online_pack<T, 2, false>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
+    auto scale_u = [&](float f) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) g.U[i][r] *= f;
+    };
+    if (MODE == kModeLazy) {
+        bool risky;
+        LazySpec spec;
+        if (general)
+            risky = lazy_spec_pack<T, 2, true, true, TL>(acc, bfrag, g.st, c_log2, jb, nvis, lane,
+                                                         spec, wary);
+        else
+            risky = lazy_spec_pack<T, 2, false, false, TL>(acc, bfrag, g.st, c_log2, jb, nvis,
+                                                           lane, spec, wary);
+        if (spec.any_moved) scale_u(spec.fu);
+        if (!spec.checked && __builtin_amdgcn_ballot_w64(risky) != 0) {
+            // rare: a flagged row's coefficients do not fit the storage type.  bf16 with a
+            // sum that is still a number: the reference moves up by a power of two and the
+            // coefficients are scaled as they are.  Else the checked step on the raw scores,
+            // which are formed again (K is still in LDS) rather than kept: holding them until
+            // here would cost the common path 32 registers.  The wavefront then looks before
+            // it exponentiates for a while (wary).
+            const bool lost = risky && !(spec.psum <= kLazyShiftMax);
+            const bool any_lost = __builtin_amdgcn_ballot_w64(lost) != 0;
+            float f;
+            if (std::is_same<T, BF16>::value && !any_lost) {
+                f = lazy_shift_inplace_bf16<TL>(bfrag, 4, g.st, risky, spec);
+            } else {
+                f32x16 acc2[2];
+                phase_scores<T, D>(ks, g, acc2);
+                bool moved;
+                if (general)
+                    f = lazy_checked_pack<T, 2, true, TL>(acc2, bfrag, g.st, risky, c_log2, jb,
+                                                          nvis, moved);
+                else
+                    f = lazy_checked_pack<T, 2, false, TL>(acc2, bfrag, g.st, risky, c_log2, jb,
+                                                           nvis, moved);
+                wary.failed();
+            }
+            scale_u(f);
+        }
+    } else if (MODE == kModeOnline) {
+        float f;
+        if (general) f = online_pack<T, 2, true>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
+        else f = online_pack<T, 2, false>(acc, bfrag, g.lam, g.beta, c_log2, jb, nvis);
+        // the accumulator is rescaled only when some row's maximum has moved
+        if (__builtin_amdgcn_ballot_w64(f != 1.0f) != 0) scale_u(f);
+    } else {
+        float f;
+        if (general) f = blend_pack<T, 2, true>(acc, bfrag, g.bl, c_log2, jb, nvis);
+        else f = blend_pack<T, 2, false>(acc, bfrag, g.bl, c_log2, jb, nvis);
+        scale_u(f);                      // o <- (1 - W) o, every tile
     }
 }
 
@@ -428,9 +451,10 @@ __device__ __forceinline__ Item next_item(const Problem& p, const TileSched& sc,
 // The three phases of one tile, with the LDS slot (PAR) a compile-time constant so that
 // every operand address is a register plus an immediate.  general: keys may be masked or
 // rows may still be empty.
-template <typename T, int D, bool ONLINE, int PAR>
+template <typename T, int D, int MODE, bool TL, int PAR>
 __device__ __forceinline__ void tile_math(const uint16_t* lds, TileRegs<D>& g, int j0, int hh,
-                                          int lane, int nvis, bool general, float c_log2) {
+                                          int lane, int nvis, bool general, float c_log2,
+                                          Wary& wary) {
     constexpr int kTile = kBC * D;
     f32x16 acc[2];
     u32x4 bfrag[4];
@@ -446,8 +470,8 @@ __device__ __forceinline__ void tile_math(const uint16_t* lds, TileRegs<D>& g, i
     // from memory per launch of the headline workload.
     wait_copies();
     if (kEarlyV) prefetch_v<D>(lds + (2 + PAR) * kTile, g, va0);
-    phase_coeffs<T, D, ONLINE>(lds + PAR * kTile, acc, bfrag, g, j0, hh, lane, nvis, general,
-                               c_log2);
+    phase_coeffs<T, D, MODE, TL>(lds + PAR * kTile, acc, bfrag, g, j0, hh, lane, nvis,
+                                          general, c_log2, wary);
     if (!kEarlyV) prefetch_v<D>(lds + (2 + PAR) * kTile, g, va0);
     phase_output<T, D>(lds + (2 + PAR) * kTile, g, bfrag, va0);
 }
@@ -457,9 +481,13 @@ __device__ __forceinline__ void tile_math(const uint16_t* lds, TileRegs<D>& g, i
 // the math of tile t, one barrier per tile.  A workgroup may own two row tiles (a long and a
 // short one under a causal mask, so that all workgroups carry the same work); the copy
 // pipeline runs on across the change of row tile.
-template <typename T, int D, bool ONLINE>
+// TL: the state is handed out (partial states, state_out) and the coefficient sums are those
+// of the rounded coefficients: also carry the unrounded sum, so that the Lam handed out is the
+// true log-sum-exp.
+template <typename T, int D, int MODE, bool TL>
 __global__ __launch_bounds__(kNW * 64, 2)
 void tile_kernel(Problem p, TileSched sc) {
+    constexpr bool kTL = TL && Mma<T>::kRoundedSum && MODE == kModeLazy;
     using C = TileCfg<D>;
     constexpr int NKK = D / 16;       // k-steps of the score product
     constexpr int NDB = D / 32;       // 32-wide blocks of the head dimension
@@ -506,6 +534,7 @@ void tile_kernel(Problem p, TileSched sc) {
 
     const float c_log2 = p.scale * kLog2e;        // scores are carried in log2 units
     const float ninf = -__builtin_inff();
+    Wary wary = {0, kWaryTiles};      // wavefront-uniform, see lazy_spec_pack
 
     for (bool first = true; cur.valid; first = false) {
         ++seq;
@@ -514,10 +543,11 @@ void tile_kernel(Problem p, TileSched sc) {
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) g.U[i][r] = 0.0f;
-        g.st = {0.0f, 1.0f, 0.0f};
+        g.st = {0.0f, 1.0f, 0.0f, 0.0f};
+        g.bl = {0.0f, 0.0f};
         g.lam = ninf;
         g.beta = 0.0f;
-        if (!ONLINE && p.from_state) {
+        if (MODE == kModeLazy && p.from_state) {
             // continue from the state of earlier keys: o = U with beta = 1, R = Lam
             const int row = min(cur.wrow0 + col, p.Lq - 1);
             const float* src = p.state_in +
@@ -533,7 +563,7 @@ void tile_kernel(Problem p, TileSched sc) {
                         g.U[i][4 * gq + 0] = x.x; g.U[i][4 * gq + 1] = x.y;
                         g.U[i][4 * gq + 2] = x.z; g.U[i][4 * gq + 3] = x.w;
                     }
-                g.st = {lam_in * kLog2e, 1.0f, 1.0f};
+                g.st = {lam_in * kLog2e, 1.0f, 1.0f, 1.0f};
             }
             // Have the state here before going on: left pending, these loads make the
             // compiler put a full wait in front of the epilogue's first use of U (a row tile
@@ -573,8 +603,8 @@ void tile_kernel(Problem p, TileSched sc) {
                 have0 = true;
             }
             if (j0 < cur.wmax)
-                tile_math<T, D, ONLINE, PAR>(lds, g, j0, hh, lane, nvis,
-                                             t == 0 || j0 + kBC > cur.wmin, c_log2);
+                tile_math<T, D, MODE, TL, PAR>(lds, g, j0, hh, lane, nvis,
+                                               t == 0 || j0 + kBC > cur.wmin, c_log2, wary);
             wait_copies();
             __syncthreads();
         };
@@ -594,9 +624,13 @@ void tile_kernel(Problem p, TileSched sc) {
 
         // ---- epilogue.  FLASH-D: the output is the state, o = beta U; Alg. 2: one division.
         float fin, lam_out;
-        if (!ONLINE) {
+        if (MODE == kModeLazy) {
             fin = g.st.beta;
-            lam_out = g.st.one == 0.0f ? ninf : g.st.R - log2_fast(g.st.beta);
+            lam_out = g.st.one == 0.0f ? ninf
+                      : kTL ? g.st.R + log2_fast(g.st.ltrue) : g.st.R - log2_fast(g.st.beta);
+        } else if (MODE == kModeBlend) {
+            fin = 1.0f;                  // U is the output
+            lam_out = g.bl.one == 0.0f ? ninf : g.bl.lam;
         } else {
             row_finish<true>(g.lam, g.beta, fin, lam_out);
         }
@@ -745,7 +779,7 @@ static bool heads_as_one(int Hq, int Hkv, int Lq) {
 }
 
 template <typename T, int D>
-static hipError_t launch_tile_t(const Problem& p_in, bool online, hipStream_t st) {
+static hipError_t launch_tile_t(const Problem& p_in, int mode, hipStream_t st) {
     Problem p = p_in;
     if (heads_as_one(p.Hq, p.Hkv, p.Lq)) {
         p.Li = make_fast_div((uint32_t)p.Lq);
@@ -754,8 +788,11 @@ static hipError_t launch_tile_t(const Problem& p_in, bool online, hipStream_t st
     }
     const long m_tiles = (p.Lq + 32 * kNW - 1) / (32 * kNW);
     if (m_tiles * p.splits * p.B * p.Hq > 0x7fffffffL) return hipErrorInvalidValue;
-    const int per_cu = online ? resident_per_cu<tile_kernel<T, D, true>>()
-                              : resident_per_cu<tile_kernel<T, D, false>>();
+    const bool tl = mode == kModeLazy && p.partial && Mma<T>::kRoundedSum;
+    const int per_cu = mode == kModeOnline  ? resident_per_cu<tile_kernel<T, D, kModeOnline, false>>()
+                       : mode == kModeBlend ? resident_per_cu<tile_kernel<T, D, kModeBlend, false>>()
+                       : tl                 ? resident_per_cu<tile_kernel<T, D, kModeLazy, true>>()
+                                            : resident_per_cu<tile_kernel<T, D, kModeLazy, false>>();
     const TileSched sc = tile_sched(p, per_cu * kCusPerXcd);
     // One workgroup per virtual workgroup, handed out by the hardware as slots free up.
     // (The kernel can also walk several virtual workgroups per workgroup, but a fixed split
@@ -763,10 +800,14 @@ static hipError_t launch_tile_t(const Problem& p_in, bool online, hipStream_t st
     // and runs a third faster, and only dynamic hand-out evens that out.)
     const long wgs = sc.total;
     dim3 grid((unsigned)wgs);
-    if (online)
-        hipLaunchKernelGGL((tile_kernel<T, D, true>), grid, dim3(kNW * 64), 0, st, p, sc);
+    if (mode == kModeOnline)
+        hipLaunchKernelGGL((tile_kernel<T, D, kModeOnline, false>), grid, dim3(kNW * 64), 0, st, p, sc);
+    else if (mode == kModeBlend)
+        hipLaunchKernelGGL((tile_kernel<T, D, kModeBlend, false>), grid, dim3(kNW * 64), 0, st, p, sc);
+    else if (tl)
+        hipLaunchKernelGGL((tile_kernel<T, D, kModeLazy, true>), grid, dim3(kNW * 64), 0, st, p, sc);
     else
-        hipLaunchKernelGGL((tile_kernel<T, D, false>), grid, dim3(kNW * 64), 0, st, p, sc);
+        hipLaunchKernelGGL((tile_kernel<T, D, kModeLazy, false>), grid, dim3(kNW * 64), 0, st, p, sc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !p.merge) return e;
     return launch_merge_splits(p, st);
@@ -781,11 +822,12 @@ long tile_workgroups(int B, int Hq, int Hkv, int Lq, int d) {
     return (long)B * Hq * ((Lq + 32 * kNW - 1) / (32 * kNW));
 }
 
-hipError_t launch_tile(const Problem& p, bool online, hipStream_t st) {
-    if (p.dtype == 1 && p.d == 64) return launch_tile_t<F16, 64>(p, online, st);
-    if (p.dtype == 1 && p.d == 128) return launch_tile_t<F16, 128>(p, online, st);
-    if (p.dtype == 2 && p.d == 64) return launch_tile_t<BF16, 64>(p, online, st);
-    if (p.dtype == 2 && p.d == 128) return launch_tile_t<BF16, 128>(p, online, st);
+hipError_t launch_tile(const Problem& p, int mode, hipStream_t st) {
+    if (mode != kModeLazy && mode != kModeOnline && mode != kModeBlend) return hipErrorInvalidValue;
+    if (p.dtype == 1 && p.d == 64) return launch_tile_t<F16, 64>(p, mode, st);
+    if (p.dtype == 1 && p.d == 128) return launch_tile_t<F16, 128>(p, mode, st);
+    if (p.dtype == 2 && p.d == 64) return launch_tile_t<BF16, 64>(p, mode, st);
+    if (p.dtype == 2 && p.d == 128) return launch_tile_t<BF16, 128>(p, mode, st);
     return hipErrorInvalidValue;
 }
 

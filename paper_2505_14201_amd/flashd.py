@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflashd.so")
 
 F32, F16, BF16 = 0, 1, 2
-VARIANT_AUTO, VARIANT_TILE, VARIANT_PER_KEY, VARIANT_ONLINE_SOFTMAX = 0, 1, 2, 3
+VARIANT_AUTO, VARIANT_TILE, VARIANT_PER_KEY, VARIANT_ONLINE_SOFTMAX, VARIANT_TILE_BLEND = 0, 1, 2, 3, 4
 MAX_SPLITS = 64
 STATIC_SCRATCH_BYTES = 32 << 20
 

@@ -15,10 +15,14 @@ pytestmark = pytest.mark.gpu
 DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
-def run_auto(q, k, v, w):
+def run_auto(q, k, v, w, variant=None):
+    """variant=None: flashd_attn_fwd as bench.py times it; else that variant, unsplit."""
     qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
     og = torch.full_like(qg, float("nan"))
-    flashd.attn_fwd(qg, kg, vg, og, w.causal, w.scale)
+    if variant is None:
+        flashd.attn_fwd(qg, kg, vg, og, w.causal, w.scale)
+    else:
+        flashd.attn_fwd_ex(qg, kg, vg, og, w.causal, w.scale, variant, 1)
     torch.cuda.synchronize()
     out = og.cpu()
     del qg, kg, vg, og
@@ -44,6 +48,9 @@ def test_causal_prefill_config_and_its_shifted_values_twin():
     q, k, v, _ = synthetic.make_qkv(w)
     rows = rows_for(w, [(0, 0), (w.B - 1, w.Hq - 1), (1, 7)], 8192, seed=21)
     compare_rows(run_auto(q, k, v, w), q, k, v, w, rows, w.name)
+    for variant in (flashd.VARIANT_TILE_BLEND, flashd.VARIANT_ONLINE_SOFTMAX):
+        compare_rows(run_auto(q, k, v, w, variant), q, k, v, w, rows[::4],
+                     f"{w.name} variant={variant}")
     # V + 1: outputs near 1, where the absolute bound of 2e-2 is a real constraint
     v1 = (v.float() + 1.0).to(v.dtype)
     compare_rows(run_auto(q, k, v1, w), q, k, v1, w, rows[::4], w.name + " (V + 1)")
@@ -71,3 +78,7 @@ def test_stability_stress_config_with_every_planted_row():
     rows = rows_for(w, [(0, 0), (1, 15)], 4096, seed=24,
                     must=[(b, h, i) for (b, h, i, _) in planted])
     compare_rows(run_auto(q, k, v, w), q, k, v, w, rows, w.name)
+    # the per-tile blend and the ablation on the same input (the variants bench.py times)
+    for variant in (flashd.VARIANT_TILE_BLEND, flashd.VARIANT_ONLINE_SOFTMAX):
+        compare_rows(run_auto(q, k, v, w, variant), q, k, v, w, rows[::2],
+                     f"{w.name} variant={variant}")

@@ -13,7 +13,7 @@ from tests.gpu_util import check, run_flashd
 
 pytestmark = pytest.mark.gpu
 
-TILE, PER_KEY, ONLINE = 1, 2, 3
+TILE, PER_KEY, ONLINE, BLEND = 1, 2, 3, 4
 DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
@@ -38,7 +38,7 @@ SHAPES = [
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE])
+@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE, BLEND])
 def test_small_shapes_half(shape, causal, d, dtype, variant):
     B, Hq, Hkv, Lq, Lk = shape
     w = synthetic.small("t", B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed=1000 + Lq * 7 + Lk + d)
@@ -101,7 +101,7 @@ def test_small_shapes_f32(shape, causal, d):
     check(got, ref, torch.float32, f"{shape} causal={causal} d={d} f32 auto")
 
 
-@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE])
+@pytest.mark.parametrize("variant", [TILE, PER_KEY, ONLINE, BLEND])
 @pytest.mark.parametrize("splits", [2, 3, 7, 0])
 @pytest.mark.parametrize("causal", [False, True])
 def test_split_k_partials_merge_to_the_same_result(variant, splits, causal):
@@ -115,7 +115,7 @@ def test_split_k_partials_merge_to_the_same_result(variant, splits, causal):
         check(got, ref, DT[dtype], f"splits={splits} variant={variant} Lq={Lq} Lk={Lk}")
 
 
-@pytest.mark.parametrize("variant", [TILE, ONLINE])
+@pytest.mark.parametrize("variant", [TILE, ONLINE, BLEND])
 @pytest.mark.parametrize("splits", [1, 2, 5, 0])
 def test_decode_shapes(variant, splits):
     """(Hq / Hkv) * Lq <= 32 query rows per kv head take the split-K decode kernel."""
@@ -143,7 +143,7 @@ def test_split_k_f32_and_more_splits_than_tiles():
     wb = synthetic.small("t", 1, 2, 1, 4, 130, 64, "bf16", True, seed=3101)
     q, k, v, _ = synthetic.make_qkv(wb)
     ref = oracle(q, k, v, True, wb.scale)
-    for variant in (TILE, ONLINE, PER_KEY):
+    for variant in (TILE, ONLINE, PER_KEY, BLEND):
         check(run_flashd(q, k, v, True, wb.scale, variant, 64), ref, torch.bfloat16)
 
 
@@ -159,7 +159,8 @@ def test_auto_entry_point_uses_cached_workspace_repeatedly():
 # ------------------------------------------------------------ method invariants ---
 
 @pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (TILE, "f16"), (PER_KEY, "f32"),
-                                           (PER_KEY, "bf16"), (ONLINE, "bf16")])
+                                           (PER_KEY, "bf16"), (ONLINE, "bf16"), (BLEND, "bf16"),
+                                           (BLEND, "f16")])
 def test_single_key_returns_its_value_bitwise(variant, dtype):
     w = synthetic.small("t", 1, 2, 2, 70, 1, 64, dtype, False, seed=4000)
     q, k, v, _ = synthetic.make_qkv(w)
@@ -168,7 +169,8 @@ def test_single_key_returns_its_value_bitwise(variant, dtype):
     assert torch.equal(got, want)
 
 
-@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (ONLINE, "f16")])
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (ONLINE, "f16"),
+                                           (BLEND, "bf16"), (BLEND, "f16")])
 def test_uniform_scores_give_the_mean_of_values(variant, dtype):
     w = synthetic.small("t", 1, 2, 1, 40, 333, 128, dtype, False, seed=4001)
     q, k, v, _ = synthetic.make_qkv(w)
@@ -179,7 +181,8 @@ def test_uniform_scores_give_the_mean_of_values(variant, dtype):
     check(got, oracle(q, k, v, False, w.scale), DT[dtype])
 
 
-@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (PER_KEY, "f16")])
+@pytest.mark.parametrize("variant,dtype", [(TILE, "bf16"), (PER_KEY, "f32"), (PER_KEY, "f16"),
+                                           (BLEND, "f16")])
 def test_key_permutation_invariance(variant, dtype):
     w = synthetic.small("t", 1, 2, 2, 130, 300, 64, dtype, False, seed=4002)
     q, k, v, _ = synthetic.make_qkv(w)
@@ -194,7 +197,8 @@ def test_key_permutation_invariance(variant, dtype):
 
 @pytest.mark.parametrize("variant,dtype,d", [(TILE, "f16", 64), (TILE, "bf16", 128),
                                              (PER_KEY, "f32", 64), (PER_KEY, "f16", 64),
-                                             (ONLINE, "f16", 64)])
+                                             (ONLINE, "f16", 64), (BLEND, "f16", 64),
+                                             (BLEND, "bf16", 128)])
 @pytest.mark.parametrize("splits", [1, 3])
 def test_huge_scores_and_dominant_keys_stay_finite_and_right(variant, dtype, d, splits):
     """Scaled scores of +-hundreds with planted dominant keys (jumps of ~ +-1000 between
@@ -230,7 +234,7 @@ def test_staircase_scores(dtype, step_nats, Lq):
     qq, kk, vv = (t.to(DT[dtype]) for t in (q, k, v))
     for causal in (False, True):
         ref = oracle(qq, kk, vv, causal, 1.0)
-        for variant, splits in ((TILE, 1), (TILE, 2), (PER_KEY, 1)):
+        for variant, splits in ((TILE, 1), (TILE, 2), (PER_KEY, 1), (BLEND, 1), (BLEND, 2)):
             got = run_flashd(qq, kk, vv, causal, 1.0, variant, splits)
             check(got, ref, DT[dtype], f"staircase {dtype} step={step_nats} Lq={Lq} "
                                        f"causal={causal} variant={variant} splits={splits}")

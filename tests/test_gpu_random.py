@@ -39,7 +39,7 @@ def test_random_forward_calls(seed):
     rng = np.random.default_rng(seed)
     for it in range(150):
         w = draw(rng, 1000 * seed + it)
-        variant = int(rng.choice([0, 1, 2, 3])) if w.dtype != "f32" else int(rng.choice([0, 2]))
+        variant = int(rng.choice([0, 1, 2, 3, 4])) if w.dtype != "f32" else int(rng.choice([0, 2]))
         splits = int(rng.choice([0, 1, 2, 5]))
         if splits > w.Lk:
             splits = 1
