@@ -95,7 +95,8 @@ def test_error_precedence_is_null_shape_dtype_headdim_gqa_align():
 
 
 def test_variant_and_split_errors():
-    assert fwd_ex(variant=4) == E_VARIANT
+    assert fwd_ex(variant=5) == E_VARIANT
+    assert fwd_ex(variant=flashd.VARIANT_TILE_BLEND, dtype=flashd.F32) == E_VARIANT
     assert fwd_ex(variant=-1) == E_VARIANT
     assert fwd_ex(variant=flashd.VARIANT_TILE, dtype=flashd.F32) == E_VARIANT
     assert fwd_ex(variant=flashd.VARIANT_ONLINE_SOFTMAX, dtype=flashd.F32) == E_VARIANT
