@@ -77,7 +77,9 @@ typedef enum {
 
 /*
  * Attention forward, Alg. 3 (Sec. III-C).  Picks the variant and the number of key splits
- * itself and takes split-K scratch memory from a grow-only cache kept per (device, stream);
+ * itself (for decode shapes in f16/bf16 the kernel of flashd_attn_fwd_skipv, which leaves out
+ * the value fetch of key blocks whose weights have all saturated at 0) and takes split-K
+ * scratch memory from a grow-only cache kept per (device, stream);
  * the first call that needs a larger cache allocates (hipMalloc), later calls do not.
  * Safe to call from several host threads; calls that share a stream share its cache and are
  * ordered by the stream.
@@ -157,6 +159,29 @@ int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o,
                         int B, int Hq, int Hkv, int Lq, int Lk, int d,
                         int causal, float scale, float kscale, float vscale, int dtype,
                         void* stream);
+
+/*
+ * Decode with the saturation skip of Sec. III-C (a weight that has saturated at 0 leaves the
+ * output as it is, so the value vector need not be loaded), for decode shapes only:
+ * (Hq / Hkv) * Lq <= 32 and f16/bf16 storage, else FLASHD_E_VARIANT.  Variant TILE's
+ * arithmetic; per 32-key block the scores are formed first, and the block's V is fetched only
+ * if, for some query row of the kv group, the block's top score lies within 2^200 of the
+ * largest s_last - ln w_last that row has reached so far (the test is on the full argument of
+ * the sigmoid, where the weight is exactly 0 in fp32, not on the paper's static range of score
+ * differences, which is an approximation).  K is always read.  The result is that of
+ * flashd_attn_fwd_ex(..., FLASHD_VARIANT_TILE, splits, ...) to the last bit on inputs where
+ * nothing is skipped, and within rounding of the fp32 accumulator otherwise.
+ *   splits, workspace, workspace_bytes   as for flashd_attn_fwd_ex (variant TILE).
+ *   counts   DEVICE pointer to two 64-bit unsigned integers, 8-byte aligned, or NULL: the
+ *            enqueued work ADDS the number of 32-key blocks it visited to counts[0] and the
+ *            number whose V it did not fetch to counts[1] (clear them yourself).
+ * Never allocates.  Other conventions and errors as for flashd_attn_fwd.
+ */
+int flashd_attn_fwd_skipv(const void* q, const void* k, const void* v, void* o,
+                          int B, int Hq, int Hkv, int Lq, int Lk, int d,
+                          int causal, float scale, int dtype, void* stream,
+                          int splits, void* workspace, size_t workspace_bytes,
+                          unsigned long long* counts);
 
 /*
  * flashd_attn_fwd for callers that cannot allocate: work recorded into a HIP graph, tight

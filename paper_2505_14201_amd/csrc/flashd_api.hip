@@ -166,6 +166,11 @@ int static_scratch(void** out) {
 
 enum class WsMode { Caller, Cache, Static };
 
+struct SkipArgs {
+    bool on = false;                 // decode kernel with the saturation skip on the V fetch
+    unsigned long long* counts = nullptr;
+};
+
 // ---- common front end --------------------------------------------------------
 
 struct StateArgs {
@@ -183,7 +188,7 @@ struct Kv8Args {
 int run(const void* q, const void* k, const void* v, void* o, const Shape& s, int causal,
         float scale, void* stream, int variant, int splits, void* workspace,
         size_t workspace_bytes, WsMode mode, const StateArgs& sa = StateArgs(),
-        const Kv8Args& k8 = Kv8Args()) {
+        const Kv8Args& k8 = Kv8Args(), const SkipArgs& sk = SkipArgs()) {
     const bool use_cache = mode == WsMode::Cache;
     if (!q || !k || !v) return FLASHD_E_NULL;
     if (!o && !(sa.on && sa.out)) return FLASHD_E_NULL;
@@ -192,11 +197,15 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o |
                            (uintptr_t)workspace | (uintptr_t)sa.in | (uintptr_t)sa.out;
     if (bits & 15u) return FLASHD_E_ALIGN;
+    if ((uintptr_t)sk.counts & 7u) return FLASHD_E_ALIGN;
     const int var = resolve_variant(s, variant);
     if (var < 0) return FLASHD_E_VARIANT;
     // fp8 K/V: the split-K decode kernel reads that storage itself; for other shapes K and V
     // are first widened (exactly) into scratch memory
     if (k8.on && s.dtype == FLASHD_F32) return FLASHD_E_VARIANT;
+    // the skip lives in the split-K decode kernel (f16/bf16, at most 32 query rows per kv head)
+    if (sk.on && (s.dtype == FLASHD_F32 || !flashd::decode_applies(s.Hq, s.Hkv, s.Lq)))
+        return FLASHD_E_VARIANT;
     const bool widen = k8.on && !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
     if (splits < 0 || splits > FLASHD_MAX_SPLITS || splits > s.Lk) return FLASHD_E_VARIANT;
     const int sp = splits == 0 ? auto_splits(s, var) : splits;
@@ -260,6 +269,7 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.from_state = 0;
     p.state_in = sa.in;
     p.state_out = sa.out;
+    p.vskip_counts = sk.counts;
     if (in_kernel) {
         p.partial = sa.out != nullptr ? 1 : 0;     // the "partial" is the state handed out
         p.store_o = o != nullptr ? 1 : 0;
@@ -272,9 +282,14 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.vscale = k8.vscale;
     if (direct && !in_kernel) p.ws = sa.out;
     hipError_t e;
-    const int tmode = var == FLASHD_VARIANT_ONLINE_SOFTMAX ? flashd::kTileModeOnline
-                     : var == FLASHD_VARIANT_TILE_BLEND   ? flashd::kTileModeBlend
-                                                          : flashd::kTileModeLazy;
+    // The automatic choice takes the decode kernel with the saturation skip: on inputs where
+    // nothing can be skipped it returns the bits of the unskipped kernel at the same speed.
+    const bool auto_skip = variant == FLASHD_VARIANT_AUTO && !k8.on && s.dtype != FLASHD_F32 &&
+                           flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
+    const int tmode = (sk.on || auto_skip)                 ? flashd::kTileModeLazySkipV
+                      : var == FLASHD_VARIANT_ONLINE_SOFTMAX ? flashd::kTileModeOnline
+                      : var == FLASHD_VARIANT_TILE_BLEND   ? flashd::kTileModeBlend
+                                                           : flashd::kTileModeLazy;
     if (var == FLASHD_VARIANT_PER_KEY) e = flashd::launch_perkey(p, st);
     else if (flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) e = flashd::launch_decode(p, tmode, st);
     else e = flashd::launch_tile(p, tmode, st);
@@ -335,6 +350,18 @@ int flashd_attn_fwd_kv8(const void* q, const void* k8, const void* v8, void* o, 
                WsMode::Cache, StateArgs(), a);
 }
 
+int flashd_attn_fwd_skipv(const void* q, const void* k, const void* v, void* o, int B, int Hq,
+                          int Hkv, int Lq, int Lk, int d, int causal, float scale, int dtype,
+                          void* stream, int splits, void* workspace, size_t workspace_bytes,
+                          unsigned long long* counts) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    SkipArgs sk;
+    sk.on = true;
+    sk.counts = counts;
+    return run(q, k, v, o, s, causal, scale, stream, FLASHD_VARIANT_TILE, splits, workspace,
+               workspace_bytes, WsMode::Caller, StateArgs(), Kv8Args(), sk);
+}
+
 int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
                       int causal, float scale, int dtype, float lo, float hi,
                       unsigned long long* counts, void* stream) {
@@ -361,6 +388,7 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.from_state = 0;
     p.state_in = nullptr;
     p.state_out = nullptr;
+    p.vskip_counts = nullptr;
     p.kv8 = 0;
     p.kscale = p.vscale = p.oscale = 1.0f;
     const hipError_t e =

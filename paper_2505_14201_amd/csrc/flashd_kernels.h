@@ -18,6 +18,8 @@ hipError_t launch_merge_splits(const Problem& p, hipStream_t st);
 // factor deferred (variant TILE), 1 = the Alg. 2 ablation, 2 = Alg. 3 with the blend applied
 // on every tile (variant TILE_BLEND).
 constexpr int kTileModeLazy = 0, kTileModeOnline = 1, kTileModeBlend = 2;
+// decode kernel only: kTileModeLazy with the saturation skip of Sec. III-C on the V fetch
+constexpr int kTileModeLazySkipV = 3;
 
 // Alg. 3 on key tiles (matrix cores, f16/bf16).  With p.splits > 1 also folds the partials.
 hipError_t launch_tile(const Problem& p, int mode, hipStream_t st);

@@ -24,7 +24,7 @@ _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
            "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
-           "flashd_attn_fwd_kv8", "flashd_attn_fwd_static")
+           "flashd_attn_fwd_kv8", "flashd_attn_fwd_static", "flashd_attn_fwd_skipv")
 
 
 class FlashdError(RuntimeError):
@@ -46,6 +46,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_attn_fwd_static.restype = i
     lib.flashd_attn_fwd_static.argtypes = base
     lib.flashd_attn_fwd_ex.restype = i
+    lib.flashd_attn_fwd_skipv.restype = i
+    lib.flashd_attn_fwd_skipv.argtypes = base + [i, p, z, p]
     lib.flashd_attn_fwd_ex.argtypes = base + [i, i, p, z]
     lib.flashd_workspace_bytes.restype = z
     lib.flashd_workspace_bytes.argtypes = [i] * 9
@@ -149,6 +151,29 @@ def attn_fwd_ex(q, k, v, o, causal: bool, scale: float, variant: int = VARIANT_A
         rc = _lib.flashd_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                      B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale), dt,
                                      st, int(variant), int(splits), ws_ptr, ws_bytes)
+    if rc != 0:
+        raise FlashdError(rc)
+
+
+def attn_fwd_skipv(q, k, v, o, causal: bool, scale: float, splits: int = 0, workspace=None,
+                   counts=None, stream=None) -> None:
+    """flashd_attn_fwd_skipv: decode with the saturation skip on the V fetch.  `counts`:
+    optional GPU int64 tensor of 2 elements that the launch adds (blocks visited, blocks whose
+    V was not fetched) to."""
+    B, Hq, Hkv, Lq, Lk, d, dt = _marshal(q, k, v, o)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous GPU tensor")
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if counts is not None and not (counts.is_cuda and counts.dtype == torch.int64
+                                   and counts.numel() >= 2 and counts.is_contiguous()):
+        raise ValueError("counts must be a contiguous GPU int64 tensor of 2 elements")
+    with torch.cuda.device(q.device):
+        rc = _lib.flashd_attn_fwd_skipv(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                        B, Hq, Hkv, Lq, Lk, d, int(bool(causal)), float(scale),
+                                        dt, _stream_ptr(stream), int(splits), ws_ptr, ws_bytes,
+                                        None if counts is None else counts.data_ptr())
     if rc != 0:
         raise FlashdError(rc)
 

@@ -36,6 +36,8 @@ class Workload:
     qk_std: float = 1.0   # Q and K are N(0, qk_std^2); V is always N(0, 1)
     plant_frac: float = 0.0  # fraction of query rows that get a dominant key 8*q
     seed: int = BASE_SEED
+    sink_gain: float = 0.0   # > 0: per (b, kv head) one early key is set to
+                             # (sink_gain / g) * sum of the group's last-position queries
 
     @property
     def scale(self) -> float:
@@ -113,13 +115,41 @@ def make_qkv(w: Workload):
                     j = int(rng.integers(0, hi + 1))
                     k[b, h, j, :] = (q[b, h, int(i), :].float() * 8.0).to(dt)
                     planted.append((b, h, int(i), j))
+    if w.sink_gain > 0.0:
+        plant_group_sinks(w, q, k)
     return q, k, v, planted
 
 
+def plant_group_sinks(w: Workload, q: torch.Tensor, k: torch.Tensor):
+    """Peaked-score decode inputs, shaped like the attention sink of LLM decoding: per
+    (b, kv head) one key among the first max(1, Lk // 64) positions (drawn from a generator of
+    its own, seed + 7919, so that Q, K, V are the draws of the same workload without sinks) is
+    set to (sink_gain / g) * sum over the g query heads of the group of their last-position
+    query, rounded to the storage type.  Its score is then about sink_gain * |q|^2 * scale / g
+    for every head of the group, far above the other keys', and every key after it has a
+    weight that is exactly zero in fp32.  Returns the positions [B, Hkv]."""
+    rng = np.random.default_rng(w.seed + 7919)
+    g = w.Hq // w.Hkv
+    pos = rng.integers(0, max(1, w.Lk // 64), size=(w.B, w.Hkv))
+    for b in range(w.B):
+        for kvh in range(w.Hkv):
+            grp = q[b, kvh * g:(kvh + 1) * g, w.Lq - 1, :].float().sum(dim=0)
+            k[b, kvh, int(pos[b, kvh]), :] = (grp * (w.sink_gain / g)).to(k.dtype)
+    return pos
+
+
+# The decode configuration with peaked scores: same shape, Q and K four times as wide, and a
+# dominant early key per kv group (plant_group_sinks): the workload the saturation skip of
+# Sec. III-C is measured on.
+PEAKED_DECODE = Workload("c4p_gqa_decode_peaked_bf16", 64, 32, 8, 1, 8192, 128, "bf16", False,
+                         qk_std=4.0, seed=BASE_SEED + 14, sink_gain=8.0)
+
+
 def small(name: str, B, Hq, Hkv, Lq, Lk, d, dtype, causal, seed, qk_std=1.0,
-          plant_frac=0.0) -> Workload:
+          plant_frac=0.0, sink_gain=0.0) -> Workload:
     """A parity-test sized workload with an explicit seed."""
-    return Workload(name, B, Hq, Hkv, Lq, Lk, d, dtype, causal, qk_std, plant_frac, seed)
+    return Workload(name, B, Hq, Hkv, Lq, Lk, d, dtype, causal, qk_std, plant_frac, seed,
+                    sink_gain)
 
 
 def sample_rows(w: Workload, n: int, seed: int, must=()):
