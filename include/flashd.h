@@ -33,8 +33,14 @@
  *     round).  State and accumulation are fp32 for all storage types.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work and return; they do not synchronise.
- *   - Every function returns a flashd_status (0 = success, negative = error).  On an error
- *     nothing has been enqueued.  Argument errors are detected before any GPU call.
+ *   - Every function returns a flashd_status (0 = success, negative = error).  Argument errors
+ *     are detected before any GPU call and leave nothing enqueued.  FLASHD_E_HIP can also come
+ *     from a kernel launch that the runtime refuses after an earlier kernel of the same call
+ *     (the fp8 widening, the main kernel before the merge of key splits) has been enqueued:
+ *     the output is then undefined, the inputs untouched.
+ *   - The entry points that take scratch memory from the cache allocate on first use and
+ *     cannot be recorded into a HIP graph before that; flashd_attn_fwd_ex and
+ *     flashd_attn_fwd_static never allocate.
  *   - For fixed inputs, variant and splits the output is bitwise reproducible.
  */
 #ifndef FLASHD_H
@@ -219,6 +225,18 @@ int flashd_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
 int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int Lq, int Lk, int d,
                       int causal, float scale, int dtype, float lo, float hi,
                       unsigned long long* counts, void* stream);
+
+/*
+ * Frees the split-K / fp8 scratch memory that flashd_attn_fwd, flashd_attn_fwd_state and
+ * flashd_attn_fwd_kv8 have cached for the CURRENT device: the live buffer of every stream
+ * that has been used and the buffers those streams have outgrown (which are kept until this
+ * call, since work enqueued earlier may still read them).  The frees wait for the device, so
+ * work already enqueued is not disturbed; do not call it while another host thread is inside
+ * one of those entry points for this device.  A host that creates and destroys streams should
+ * call it now and then: the cache is keyed by stream handle and forgets nothing by itself.
+ * Returns FLASHD_OK, or FLASHD_E_HIP if a free failed.
+ */
+int flashd_release_workspace(void);
 
 /* Static, NUL-terminated description of a status code. */
 const char* flashd_status_string(int status);

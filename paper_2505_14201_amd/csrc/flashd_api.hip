@@ -6,6 +6,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 #include "../../include/flashd.h"
 #include "flashd_common.h"
@@ -108,10 +109,15 @@ int check_arch() {
 }
 
 // ---- workspace cache: grow-only, one buffer per (device, stream) -----------
-// A buffer that is outgrown is kept until the process ends, because work
-// enqueued earlier on the stream may still be reading it.
+// A buffer that is outgrown is not freed on the spot, because work enqueued earlier on the
+// stream may still be reading it: it is kept in the entry's list of retired buffers until
+// flashd_release_workspace() frees everything (hipFree waits for the device first).
 
-struct CacheEntry { void* ptr = nullptr; size_t bytes = 0; };
+struct CacheEntry {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    std::vector<void*> retired;
+};
 std::map<std::pair<int, void*>, CacheEntry> g_cache;
 
 int cached_workspace(void* stream, size_t bytes, void** out) {
@@ -130,11 +136,29 @@ int cached_workspace(void* stream, size_t bytes, void** out) {
             want = bytes;
             if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
         }
+        if (e.ptr != nullptr) e.retired.push_back(e.ptr);
         e.ptr = p;
         e.bytes = want;
     }
     *out = e.ptr;
     return FLASHD_OK;
+}
+
+// Frees every cached buffer of the current device, live or retired.
+int release_workspace() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return FLASHD_E_HIP; }
+    std::lock_guard<std::mutex> lk(g_mu);
+    int rc = FLASHD_OK;
+    for (auto it = g_cache.begin(); it != g_cache.end();) {
+        if (it->first.first != dev) { ++it; continue; }
+        CacheEntry& e = it->second;
+        if (e.ptr != nullptr) e.retired.push_back(e.ptr);
+        for (void* q : e.retired)
+            if (hipFree(q) != hipSuccess) { (void)hipGetLastError(); rc = FLASHD_E_HIP; }
+        it = g_cache.erase(it);
+    }
+    return rc;
 }
 
 // ---- static scratch: split-K partial states for the entry point that allocates nothing ---
@@ -412,6 +436,8 @@ size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int
     if (var < 0 || splits < 0 || splits > FLASHD_MAX_SPLITS || splits > Lk) return 0;
     return ws_bytes(s, splits == 0 ? auto_splits(s, var) : splits);
 }
+
+int flashd_release_workspace(void) { return release_workspace(); }
 
 const char* flashd_status_string(int status) {
     switch (status) {

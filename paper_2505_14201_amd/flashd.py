@@ -24,7 +24,8 @@ _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
            "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
-           "flashd_attn_fwd_kv8", "flashd_attn_fwd_static", "flashd_attn_fwd_skipv")
+           "flashd_attn_fwd_kv8", "flashd_attn_fwd_static", "flashd_attn_fwd_skipv",
+           "flashd_release_workspace")
 
 
 class FlashdError(RuntimeError):
@@ -59,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_attn_fwd_kv8.argtypes = [p, p, p, p, i, i, i, i, i, i, i, f, f, f, i, p]
     lib.flashd_skip_stats.restype = i
     lib.flashd_skip_stats.argtypes = [p, p, i, i, i, i, i, i, i, f, i, f, f, p, p]
+    lib.flashd_release_workspace.restype = i
+    lib.flashd_release_workspace.argtypes = []
     lib.flashd_status_string.restype = ctypes.c_char_p
     lib.flashd_status_string.argtypes = [i]
     lib.flashd_version.restype = i
@@ -80,6 +83,13 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(_lib.flashd_version())
+
+
+def release_workspace() -> None:
+    """flashd_release_workspace: free the scratch memory cached for the current device."""
+    rc = int(_lib.flashd_release_workspace())
+    if rc != 0:
+        raise FlashdError(rc)
 
 
 def workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dtype, variant=VARIANT_AUTO, splits=0) -> int:

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from oracle import attention as oa
-from paper_2505_14201_amd import synthetic
+from paper_2505_14201_amd import flashd, synthetic
 from tests.gpu_util import check, run_flashd
 
 pytestmark = pytest.mark.gpu
@@ -408,3 +408,25 @@ def test_maximum_number_of_splits(shape, variant, dtype, causal):
     ref = oracle(q, k, v, causal, w.scale)
     got = run_flashd(q, k, v, causal, w.scale, variant, 64)
     check(got, ref, DT[dtype], f"{shape} {dtype} variant={variant} causal={causal}")
+
+
+def test_cached_workspace_can_be_released_and_grows_again():
+    """flashd_release_workspace frees the per-stream scratch (live and outgrown buffers); the
+    next call that needs scratch allocates afresh and gives the same result."""
+    w = synthetic.small("t", 2, 8, 2, 1, 3000, 128, "bf16", False, seed=3210)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, False, w.scale)
+    side = torch.cuda.Stream()
+    for round_ in range(2):
+        for Lk in (700, 3000):                   # grows once: one buffer retired
+            a = run_flashd(q, k[:, :, :Lk].contiguous(), v[:, :, :Lk].contiguous(), False, w.scale,
+                           use_ex=False)
+        check(a, ref, torch.bfloat16, f"round {round_}")
+        with torch.cuda.stream(side):
+            qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+            og = torch.empty_like(qg)
+            flashd.attn_fwd(qg, kg, vg, og, False, w.scale)
+        torch.cuda.synchronize()
+        check(og.cpu(), ref, torch.bfloat16, f"side stream, round {round_}")
+        flashd.release_workspace()
+    flashd.release_workspace()                   # nothing left: still fine
