@@ -433,6 +433,29 @@ def main() -> int:
                                                  "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                                  "frac": round(gbs8 / PEAK_HBM_GBS, 4),
                                                  "traffic": None}}
+        if not args.no_decode16:
+            # one sequence with a long context: 8 workgroups' worth of (b, kv head) units, so
+            # the keys are split 64 ways and merge_splits_kernel folds the partial states
+            gen = torch.Generator().manual_seed(wd.seed + 17)
+            Ll = 131072
+            q1 = torch.randn((1, wd.Hq, 1, wd.d), generator=gen).to(qg.dtype).cuda()
+            k1 = torch.randn((1, wd.Hkv, Ll, wd.d), generator=gen).to(qg.dtype).cuda()
+            v1 = torch.randn((1, wd.Hkv, Ll, wd.d), generator=gen).to(qg.dtype).cuda()
+            o1 = torch.empty_like(q1)
+
+            def step_long(_):
+                flashd.attn_fwd(q1, k1, v1, o1, False, wd.scale)
+            _, evl = time_calls(step_long, dsteps, 5, 1)
+            msl = evl / dsteps
+            bytesl = (k1.numel() + v1.numel() + 2 * q1.numel()) * k1.element_size()
+            out["decode_single_sequence_128k"] = {
+                "ms_per_step": round(msl, 4), "bytes_per_step": bytesl,
+                "splits": flashd.auto_splits(1, wd.Hq, wd.Hkv, 1, Ll, wd.d, flashd.BF16),
+                "roofline": {"bound": "hbm", "achieved": round(bytesl / (msl * 1e-3) / 1e9, 1),
+                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(bytesl / (msl * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                             "traffic": None}}
+            del q1, k1, v1, o1
         if not args.no_skipv:
             # Saturation skip of Sec. III-C on the V fetch, on the decode shape with peaked
             # scores (a dominant early key per kv group): the kernel with and without the skip
