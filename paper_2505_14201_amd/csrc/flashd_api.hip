@@ -44,6 +44,11 @@ int resolve_variant(const Shape& s, int variant) {
 
 int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
+// n partial states (o[d], s, ln w) per query row
+size_t partial_bytes(const Shape& s, int n) {
+    return (size_t)n * s.B * s.Hq * s.Lq * (size_t)(s.d + 2) * sizeof(float);
+}
+
 // Splits for the automatic choice: enough independent work to fill 256 compute units, but
 // never key ranges shorter than 256 keys.
 int auto_splits(const Shape& s, int variant) {
@@ -69,19 +74,25 @@ int auto_splits(const Shape& s, int variant) {
     // split; the tile kernel's workgroups carry 128 rows each, and measured over prefill
     // shapes a split only pays once it still holds some 2048 keys (B1 H32 L1024 causal:
     // 23 us unsplit, 39 us in two splits of 512 keys).
+    // With few query rows in all (short queries that do not fit the decode kernel: 4 x 8
+    // heads x 8 positions over 4096 keys runs 15 us in 16 splits, 45 us in 2) the partial
+    // states are small again: splits of 256 keys are allowed as long as all the partial
+    // states together stay within some 40 MB.
     const bool tile = variant != FLASHD_VARIANT_PER_KEY &&
                       !flashd::decode_applies(s.Hq, s.Hkv, s.Lq);
-    const long min_keys = tile ? 2048 : 256;
-    const long by_len = s.Lk / min_keys > 0 ? s.Lk / min_keys : 1;
+    long by_len = s.Lk / (tile ? 2048 : 256);
+    if (tile) {
+        const long double per_split = (long double)partial_bytes(s, 1) * 2.0L;   // written and read
+        const long by_bytes = per_split > 0.0L ? (long)(40.0e6L / per_split) : 0;
+        const long by_len_short = s.Lk / 256;
+        const long few_rows = by_bytes < by_len_short ? by_bytes : by_len_short;
+        if (few_rows > by_len) by_len = few_rows;
+    }
+    if (by_len < 1) by_len = 1;
     if (sp > by_len) sp = by_len;
     if (sp > FLASHD_MAX_SPLITS) sp = FLASHD_MAX_SPLITS;
     if (sp < 1) sp = 1;
     return (int)sp;
-}
-
-// n partial states (o[d], s, ln w) per query row
-size_t partial_bytes(const Shape& s, int n) {
-    return (size_t)n * s.B * s.Hq * s.Lq * (size_t)(s.d + 2) * sizeof(float);
 }
 
 size_t ws_bytes(const Shape& s, int splits) { return splits <= 1 ? 0 : partial_bytes(s, splits); }

@@ -125,6 +125,18 @@ def test_workspace_errors_and_sizes():
             flashd.workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dt, 0, s)
 
 
+def test_automatic_splits_follow_the_size_of_the_partial_states():
+    # few query rows in all: short key ranges per split are worth it
+    assert flashd.auto_splits(4, 8, 1, 8, 4096, 128, flashd.BF16) >= 8
+    # one row tile of partial states per 128 rows: a split must keep 2048 keys
+    assert flashd.auto_splits(1, 32, 32, 1024, 1024, 128, flashd.BF16) == 1
+    assert flashd.auto_splits(4, 32, 32, 2048, 2048, 128, flashd.BF16) == 1
+    assert flashd.auto_splits(1, 32, 8, 128, 32768, 128, flashd.BF16) == 16
+    # decode: 256 keys are enough, and one round of 512 workgroups is the aim
+    assert flashd.auto_splits(1, 32, 8, 1, 32768, 128, flashd.BF16) == 64
+    assert flashd.auto_splits(64, 32, 8, 1, 8192, 128, flashd.BF16) == 1
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a machine without a GPU")
 def test_valid_arguments_without_a_gpu_report_hip_error():
     assert fwd() == E_HIP

@@ -391,6 +391,21 @@ def test_query_heads_of_a_kv_group_run_as_one_head(shape, causal, variant, dtype
         assert torch.count_nonzero(got[:, :, :Lq - Lk]) == 0, "rows without keys must be zeros"
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f16", 64)])
+def test_short_queries_take_many_splits_through_the_automatic_entry_point(dtype, d):
+    """8 heads x 8 positions per kv head are too many rows for the decode kernel; the tile
+    kernel runs them as one head, and with so few rows in all the automatic choice cuts the
+    keys into many splits."""
+    B, Hq, Hkv, Lq, Lk = 2, 8, 1, 8, 3000
+    from paper_2505_14201_amd import flashd
+    assert flashd.auto_splits(B, Hq, Hkv, Lq, Lk, d, flashd._DTYPE[DT[dtype]]) >= 8
+    w = synthetic.small("short queries", B, Hq, Hkv, Lq, Lk, d, dtype, True, seed=8900 + d)
+    q, k, v, _ = synthetic.make_qkv(w)
+    ref = oracle(q, k, v, True, w.scale)
+    got = run_flashd(q, k, v, True, w.scale, use_ex=False)
+    check(got, ref, DT[dtype], f"short queries {dtype} d={d}")
+
+
 @pytest.mark.parametrize("shape,variant,dtype", [
     ((2, 8, 2, 1, 5000), TILE, "bf16"),        # decode kernel, 64 partials per row
     ((1, 4, 4, 150, 4500), TILE, "f16"),       # tile kernel
