@@ -76,9 +76,17 @@ typedef enum {
     FLASHD_VARIANT_PER_KEY = 2,  /* Alg. 3 literally, one sigmoid per key (any dtype)       */
     FLASHD_VARIANT_ONLINE_SOFTMAX = 3, /* ablation: Alg. 2 (running max, sum, final division)
                                           on the same tiling as TILE (f16/bf16)             */
-    FLASHD_VARIANT_TILE_BLEND = 4      /* Alg. 3 on key tiles with the blend of Sec. III-A applied
+    FLASHD_VARIANT_TILE_BLEND = 4,     /* Alg. 3 on key tiles with the blend of Sec. III-A applied
                                           on every tile: o <- (1 - W) o + sum_j c_j v_j with
                                           W = sigmoid(Lam_tile - Lam) and c_j <= 1 (f16/bf16)  */
+    FLASHD_VARIANT_TILE_256 = 5        /* TILE on the kernel with 256 query rows per workgroup
+                                          (one wavefront per SIMD, matrix and vector work
+                                          interleaved by hand) where it can serve the call:
+                                          f16/bf16, d = 128, Lq a multiple of 256, no splits,
+                                          no state; any other call runs as TILE.  Same
+                                          arithmetic; measured about level with TILE on long
+                                          unmasked inputs and slower under a causal mask, so
+                                          it is never chosen automatically                  */
 } flashd_variant;
 
 /*

@@ -7,9 +7,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashd.so")
-SOURCES = ("flashd_api.hip", "flashd_perkey.hip", "flashd_tile.hip", "flashd_decode.hip",
+SOURCES = ("flashd_api.hip", "flashd_perkey.hip", "flashd_tile.hip", "flashd_wide.hip", "flashd_decode.hip",
            "flashd_stats.hip", "flashd_widen.hip")
-HEADERS = ("flashd_common.h", "flashd_kernels.h", "flashd_mma.h", os.path.join("..", "..", "include", "flashd.h"))
+HEADERS = ("flashd_common.h", "flashd_kernels.h", "flashd_mma.h", "flashd_tile_parts.h", "flashd_wide_regs.h", os.path.join("..", "..", "include", "flashd.h"))
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

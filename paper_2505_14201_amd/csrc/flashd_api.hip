@@ -35,7 +35,7 @@ int validate_shape(const Shape& s) {
 }
 
 int resolve_variant(const Shape& s, int variant) {
-    if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_TILE_BLEND) return -1;
+    if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_TILE_256) return -1;
     if (variant == FLASHD_VARIANT_AUTO)
         return s.dtype == FLASHD_F32 ? FLASHD_VARIANT_PER_KEY : FLASHD_VARIANT_TILE;
     if (s.dtype == FLASHD_F32 && variant != FLASHD_VARIANT_PER_KEY) return -1;
@@ -305,6 +305,7 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.state_in = sa.in;
     p.state_out = sa.out;
     p.vskip_counts = sk.counts;
+    p.wide = var == FLASHD_VARIANT_TILE_256 ? 1 : 0;
     if (in_kernel) {
         p.partial = sa.out != nullptr ? 1 : 0;     // the "partial" is the state handed out
         p.store_o = o != nullptr ? 1 : 0;
@@ -423,6 +424,7 @@ int flashd_skip_stats(const void* q, const void* k, int B, int Hq, int Hkv, int 
     p.from_state = 0;
     p.state_in = nullptr;
     p.state_out = nullptr;
+    p.wide = 0;
     p.vskip_counts = nullptr;
     p.kv8 = 0;
     p.kscale = p.vscale = p.oscale = 1.0f;

@@ -55,6 +55,7 @@ struct Problem {
     float oscale;       // factor on the output (and on the o of partial states); 1 unless kv8
     const float* state_in;   // optional state of earlier keys, [B][Hq][Lq][d + 2] fp32
     float* state_out;        // optional state after this call's keys, same layout
+    int wide;           // 1: the tiled prefill takes the 256-row kernel where it can serve the call
     unsigned long long* vskip_counts;   // optional, decode kernel with saturation skips:
                                         // [0] += 32-key blocks visited, [1] += blocks whose V was not fetched
     FastDiv Li;         // causal rule: row r of a head stands for query position r % Li.d.  Li.d == Lq

@@ -60,6 +60,10 @@ template <> struct Mma<BF16> {
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, bf16x4));
     }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+    }
     // two fp8 (e4m3) values of a dword -> two storage-type values, exact (scale 1)
     static __device__ __forceinline__ uint32_t from_fp8_lo(uint32_t w) {
         return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
@@ -86,6 +90,11 @@ template <> struct Mma<F16> {
     }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, f16x4));
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, f16x2));
     }
     static __device__ __forceinline__ uint32_t from_fp8_lo(uint32_t w) {
         return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false));

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libflashd.so")
 
 F32, F16, BF16 = 0, 1, 2
 VARIANT_AUTO, VARIANT_TILE, VARIANT_PER_KEY, VARIANT_ONLINE_SOFTMAX, VARIANT_TILE_BLEND = 0, 1, 2, 3, 4
+VARIANT_TILE_256 = 5
 MAX_SPLITS = 64
 STATIC_SCRATCH_BYTES = 32 << 20
 

@@ -95,8 +95,9 @@ def test_error_precedence_is_null_shape_dtype_headdim_gqa_align():
 
 
 def test_variant_and_split_errors():
-    assert fwd_ex(variant=5) == E_VARIANT
+    assert fwd_ex(variant=6) == E_VARIANT
     assert fwd_ex(variant=flashd.VARIANT_TILE_BLEND, dtype=flashd.F32) == E_VARIANT
+    assert fwd_ex(variant=flashd.VARIANT_TILE_256, dtype=flashd.F32) == E_VARIANT
     assert fwd_ex(variant=-1) == E_VARIANT
     assert fwd_ex(variant=flashd.VARIANT_TILE, dtype=flashd.F32) == E_VARIANT
     assert fwd_ex(variant=flashd.VARIANT_ONLINE_SOFTMAX, dtype=flashd.F32) == E_VARIANT
