@@ -154,11 +154,15 @@ def oracle_leg(w, host, got, budget_flop=2.0e12):
 
 
 def variant_legs(w, sets, steps, warmup):
-    """Kernel time of the Alg. 2 ablation and of the per-tile blend on the same inputs."""
+    """Kernel time of the Alg. 2 ablation, of the per-tile blend and (d = 128, where it applies)
+    of the 256-row kernel on the same inputs."""
     from paper_2505_14201_amd import flashd
     out = {}
-    for key, var in (("ablation_online_softmax", flashd.VARIANT_ONLINE_SOFTMAX),
-                     ("tile_blend", flashd.VARIANT_TILE_BLEND)):
+    legs = [("ablation_online_softmax", flashd.VARIANT_ONLINE_SOFTMAX),
+            ("tile_blend", flashd.VARIANT_TILE_BLEND)]
+    if w.d == 128 and w.Lq % 256 == 0:
+        legs.append(("tile_256_rows", flashd.VARIANT_TILE_256))
+    for key, var in legs:
         def step_var(i, var=var):
             qg, kg, vg, og = sets[i]
             flashd.attn_fwd_ex(qg, kg, vg, og, w.causal, w.scale, var, 1)

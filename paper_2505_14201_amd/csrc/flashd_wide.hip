@@ -94,42 +94,6 @@ __device__ __forceinline__ void wide_copy(const uint16_t* src, int j0, int Lk, c
 // constant once the loops around them are unrolled.  The compiler does not see these as
 // matrix instructions, so a result is only read by vector instructions that are known to come
 // at least 20 wait states later (mma_fence() where nothing else lies between).
-template <typename T>
-__device__ __forceinline__ void wq_first(int n, f32x16& acc, u32x4 k) {
-    switch (n) {
-#define FLASHD_CASE(N) case N: WideQ<T, N>::first(acc, k); break;
-        FLASHD_CASE(0) FLASHD_CASE(1) FLASHD_CASE(2) FLASHD_CASE(3) FLASHD_CASE(4) FLASHD_CASE(5)
-        FLASHD_CASE(6) FLASHD_CASE(7) FLASHD_CASE(8) FLASHD_CASE(9) FLASHD_CASE(10) FLASHD_CASE(11)
-        FLASHD_CASE(12) FLASHD_CASE(13) FLASHD_CASE(14) FLASHD_CASE(15)
-#undef FLASHD_CASE
-    }
-}
-template <typename T>
-__device__ __forceinline__ void wq_next(int n, f32x16& acc, u32x4 k) {
-    switch (n) {
-#define FLASHD_CASE(N) case N: WideQ<T, N>::next(acc, k); break;
-        FLASHD_CASE(0) FLASHD_CASE(1) FLASHD_CASE(2) FLASHD_CASE(3) FLASHD_CASE(4) FLASHD_CASE(5)
-        FLASHD_CASE(6) FLASHD_CASE(7) FLASHD_CASE(8) FLASHD_CASE(9) FLASHD_CASE(10) FLASHD_CASE(11)
-        FLASHD_CASE(12) FLASHD_CASE(13) FLASHD_CASE(14) FLASHD_CASE(15)
-#undef FLASHD_CASE
-    }
-}
-// acc (scores of row block rb) = / += K operand kk times the row block's Q fragment kk
-template <typename T>
-__device__ __forceinline__ void wq_mma(int rb, int kk, f32x16& acc, u32x4 k) {
-    if (kk == 0) wq_first<T>(8 * rb + kk, acc, k);
-    else wq_next<T>(8 * rb + kk, acc, k);
-}
-// U[rb][i] += a b
-template <typename T>
-__device__ __forceinline__ void wu_mma(int rb, int i, u32x4 a, u32x4 b) {
-    switch (4 * rb + i) {
-#define FLASHD_CASE(J) case J: WideU<T, J>::mma(a, b); break;
-        FLASHD_CASE(0) FLASHD_CASE(1) FLASHD_CASE(2) FLASHD_CASE(3) FLASHD_CASE(4) FLASHD_CASE(5)
-        FLASHD_CASE(6) FLASHD_CASE(7)
-#undef FLASHD_CASE
-    }
-}
 __device__ __forceinline__ void wide_set_q_n(int n, u32x4 q) {
     switch (n) {
 #define FLASHD_CASE(N) case N: wide_set_q<N>(q); break;
@@ -222,19 +186,36 @@ __device__ __forceinline__ void mma_fence(f32x16 (&acc)[kWideRB]) {
     asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0]), "+v"(acc[1]));
 }
 
-// Raw scores of one 32-key block (kb: its rows in LDS) for both row blocks: every K operand
-// feeds two matrix instructions.
+// Copy instruction N (of DmaLane::NI) of the same, for a tile that lies wholly inside the keys:
+// the fused steps issue the copies of a period one at a time, spread over the period (issued
+// together by the four wavefronts of the workgroup, which run in step, 32 of these queue up in
+// front of the one address unit), and without a branch in between.
+template <int D, bool IS_V, int N>
+__device__ __forceinline__ void wide_copy_one(const uint16_t* src, int j0, const DmaLane<D>& dl,
+                                              int wave, uint16_t* dst) {
+    constexpr int NI = DmaLane<D>::NI;
+    static_assert(N < NI, "a tile takes NI copy instructions per wavefront");
+    uint16_t* w = dst + wave * (NI * 512);
+    const char* t = reinterpret_cast<const char*>(src + (size_t)j0 * D);
+    uint32_t off = IS_V ? dl.voff : dl.koff[N];
+    asm volatile("" : "+v"(off));
+    __builtin_amdgcn_global_load_lds((gptr_t)(t + off), (lptr_t)w, 16, 1024 * N, 0);
+}
+
+// Raw scores of one 32-key block (kb: its rows in LDS) for both row blocks, by plain steps:
+// all eight K operands into the operand ring, then the sixteen matrix instructions (every
+// operand feeds two).
 template <typename T, int D>
 __device__ __forceinline__ void wide_scores(const uint16_t* kb, const WideRegs<D>& g,
                                             f32x16 (&acc)[kWideRB]) {
     constexpr int NKK = D / 16;
-    u32x4 ka[NKK];
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) ka[kk] = *reinterpret_cast<const u32x4*>(&kb[g.kaddr[kk]]);
+    for (int kk = 0; kk < NKK; ++kk) wide_req_k<D>(kk, kb, g);
+    wide_wait_lds<0>();
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
-        for (int rb = 0; rb < kWideRB; ++rb) wq_mma<T>(rb, kk, acc[rb], ka[kk]);
+        for (int rb = 0; rb < kWideRB; ++rb) ws_mma<T>(rb, kk, acc[rb]);
     mma_fence(acc);
 }
 
@@ -259,7 +240,6 @@ struct WideCoef {
     f32x4 ps[kWideRB];
     float ref[kWideRB], f[kWideRB];
     bool empty[kWideRB];
-    u32x4 va03[4];              // V operands requested ahead (the fused steps: the first three)
 };
 
 // What one fused step hands to the next: the K operands of the next score product (requested
@@ -366,11 +346,12 @@ __device__ __forceinline__ void wide_h1(const WideAhead& ah, const uint16_t* kb,
 // row state,
 //     1/beta' = 1/beta + psum,
 // and look at the top scores of the next block (accn): ah.bail.  Pipelined like wide_h1.
-template <typename T, int D>
+// copy_hook(i), i = 0..3: called in slots 1, 5, 9, 13, for the caller's global->LDS copies.
+template <typename T, int D, typename Hook>
 __device__ __forceinline__ void wide_h2(const uint16_t* vb, const uint16_t* kb_ahead,
                                         WideRegs<D>& g, const f32x16 (&acc)[kWideRB],
                                         const f32x16 (&accn)[kWideRB], float c_log2, WideCoef& c,
-                                        WideAhead& ah) {
+                                        WideAhead& ah, const Hook& copy_hook) {
     static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
     constexpr int NDB = D / 32;
     constexpr int NV = 2 * NDB;
@@ -408,6 +389,7 @@ __device__ __forceinline__ void wide_h2(const uint16_t* vb, const uint16_t* kb_a
         // V operand 3 + s / 2 (used in slot 6 + s), then the first K operands of the next step
         if (s <= 8 && (s & 1) == 0) wide_req_v<D>(3 + (s >> 1), vb, g);
         if (s >= 10 && (s & 1) == 0) wide_req_k<D>((s - 10) >> 1, kb_ahead, g);
+        if ((s & 3) == 1) copy_hook(s >> 2);
         if (s < 8) { F(s + 1); X(s); A(s - 1); }
         if (s == 8) A(7);
         // the look at the next block: two maxima per row block and slot
@@ -496,8 +478,7 @@ __device__ __forceinline__ void wide_first_general(const uint16_t* vb, WideRegs<
 #pragma unroll
         for (int e = 0; e < 8; ++e) c.ps[rb][e & 3] += pv0[e];
     }
-#pragma unroll
-    for (int m = 0; m < 4; ++m) c.va03[m] = tile_v_operand<D>(vb, g.vaddr[m], 0);
+    (void)vb;
 }
 
 // Second half of a block's step by plain steps: the output product U <- U + P V over the
@@ -507,12 +488,8 @@ template <typename T, int D>
 __device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, WideCoef& c) {
     constexpr int NDB = D / 32;
     constexpr int NV = 2 * NDB;
-    static_assert(NDB == 4, "four operands per 16 keys");
-    u32x4 va[NV];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) va[m] = c.va03[m];
-#pragma unroll
-    for (int m = 4; m < NV; ++m) va[m] = tile_v_operand<D>(vb, g.vaddr[m % NDB], 16);
+    for (int m = 0; m < NV; ++m) wide_req_v<D>(m, vb, g);
     u32x4 bf1[kWideRB];
 #pragma unroll
     for (int rb = 0; rb < kWideRB; ++rb) {
@@ -527,11 +504,14 @@ __device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, 
         g.st[rb].R = has ? c.ref[rb] : g.st[rb].R;
         g.st[rb].one = has ? 1.0f : g.st[rb].one;
     }
+    wide_wait_lds<0>();
+    // the coefficients were packed by vector instructions just now: two wait states before the
+    // first matrix instruction reads them
+    asm volatile("s_nop 1");
 #pragma unroll
     for (int m = 0; m < NV; ++m)
 #pragma unroll
-        for (int rb = 0; rb < kWideRB; ++rb)
-            wu_mma<T>(rb, m % NDB, va[m], m / NDB == 0 ? c.bf0[rb] : bf1[rb]);
+        for (int rb = 0; rb < kWideRB; ++rb) wp_mma<T>(rb, m, m / NDB == 0 ? c.bf0[rb] : bf1[rb]);
 }
 
 // LDS: four K slots and three V slots.  A wavefront forms the scores of block b + 1 while it
@@ -645,16 +625,33 @@ void wide_kernel(Problem p, TileSched sc) {
             const int vslot1 = vslot == 2 ? 0 : vslot + 1;
             const int vslot2 = vslot1 == 2 ? 0 : vslot1 + 1;
             const int j0 = cur.jbase + t * kBC;
-            int started = 0;                // copy instructions of this period
-            if (t + 3 < n) {
-                wide_copy<D, false>(cur.kg, j0 + 3 * kBC, p.Lk, dl, wave, lane,
-                                    lds + ((t + 3) & 3) * kTile);
-                started += DmaLane<D>::NI;
-            }
-            if (t + 2 < n) {
-                wide_copy<D, true>(cur.vg, j0 + 2 * kBC, p.Lk, dl, wave, lane, vs0 + vslot2 * kTile);
-                started += DmaLane<D>::NI;
-            }
+            // this period's copies: K(t + 3) and V(t + 2).  A fused period issues them one at
+            // a time from its output-product slots, K from the first block's, V from the
+            // second's; whatever has not gone out that way goes out in one piece after the blocks.
+            const bool kcopy = t + 3 < n, vcopy = t + 2 < n;
+            // (one at a time only for tiles that lie wholly inside the keys)
+            const bool kspread = kcopy && j0 + 4 * kBC <= p.Lk;
+            const bool vspread = vcopy && j0 + 3 * kBC <= p.Lk;
+            bool kdone = false, vdone = false;
+            uint16_t* const kdst = lds + ((t + 3) & 3) * kTile;
+            uint16_t* const vdst = vs0 + vslot2 * kTile;
+            auto khook = [&](int i) __attribute__((always_inline)) {
+                switch (i) {
+                    case 0: wide_copy_one<D, false, 0>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
+                    case 1: wide_copy_one<D, false, 1>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
+                    case 2: wide_copy_one<D, false, 2>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
+                    default: wide_copy_one<D, false, 3>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
+                }
+            };
+            auto vhook = [&](int i) __attribute__((always_inline)) {
+                switch (i) {
+                    case 0: wide_copy_one<D, true, 0>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
+                    case 1: wide_copy_one<D, true, 1>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
+                    case 2: wide_copy_one<D, true, 2>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
+                    default: wide_copy_one<D, true, 3>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
+                }
+            };
+            auto nohook = [](int) __attribute__((always_inline)) {};
             const uint16_t* kcur = lds + (t & 3) * kTile;
             const uint16_t* knext = lds + ((t + 1) & 3) * kTile;
             const uint16_t* vcur = vs0 + vslot * kTile;
@@ -664,11 +661,18 @@ void wide_kernel(Problem p, TileSched sc) {
                 if (__builtin_expect(!ah.bail, 1)) {
                     WideCoef c;
                     wide_h1<T, D>(ah, kcur + kWideKB * D, vcur, g, acc[0], acc[1], c_log2, c);
-                    wide_h2<T, D>(vcur, knext, g, acc[0], acc[1], c_log2, c, ah);
+                    if (kspread) wide_h2<T, D>(vcur, knext, g, acc[0], acc[1], c_log2, c, ah, khook);
+                    else wide_h2<T, D>(vcur, knext, g, acc[0], acc[1], c_log2, c, ah, nohook);
+                    kdone = kspread;
                     if (__builtin_expect(!ah.bail, 1)) {
                         wide_h1<T, D>(ah, knext, vcur + kWideKB * D, g, acc[1], acc[0], c_log2, c);
-                        wide_h2<T, D>(vcur + kWideKB * D, knext + kWideKB * D, g, acc[1], acc[0], c_log2, c,
-                                      ah);
+                        if (vspread)
+                            wide_h2<T, D>(vcur + kWideKB * D, knext + kWideKB * D, g, acc[1], acc[0],
+                                          c_log2, c, ah, vhook);
+                        else
+                            wide_h2<T, D>(vcur + kWideKB * D, knext + kWideKB * D, g, acc[1], acc[0],
+                                          c_log2, c, ah, nohook);
+                        vdone = vspread;
                         have_ah = true;
                     } else {
                         step(IntC<1>{}, t, kcur, knext, vcur);
@@ -682,6 +686,9 @@ void wide_kernel(Problem p, TileSched sc) {
                 step(IntC<1>{}, t, kcur, knext, vcur);
                 have_ah = false;
             }
+            if (kcopy && !kdone) wide_copy<D, false>(cur.kg, j0 + 3 * kBC, p.Lk, dl, wave, lane, kdst);
+            if (vcopy && !vdone) wide_copy<D, true>(cur.vg, j0 + 2 * kBC, p.Lk, dl, wave, lane, vdst);
+            const int started = (kcopy ? 4 : 0) + (vcopy ? 4 : 0);   // copy instructions of this period
             static_assert(DmaLane<D>::NI == 4, "the waits below count 4 copies per tile and tensor");
             if (started == 8) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);       // vmcnt(8)
             else if (started == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);  // vmcnt(4)
