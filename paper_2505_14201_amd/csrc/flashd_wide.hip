@@ -1,8 +1,8 @@
-// The tiled FLASH-D prefill kernel for long inputs: 64 query rows per wavefront.
+// The tiled FLASH-D prefill kernel with 256 query rows per workgroup (variant TILE_256).
 //
 // Same tile form of Alg. 3 (Sec. III-A/B lifted to key tiles, see flashd_tile.hip and
-// flashd_mma.h), same LDS layout, copies and work hand-out as the 128-row kernel.  What differs
-// is the shape of a workgroup and the order of the work inside a tile:
+// flashd_mma.h), same LDS layout of a tile, same copies and work hand-out as the 128-row
+// kernel.  What differs is the shape of a workgroup and the order of the work:
 //
 //   * A wavefront owns two 32-row blocks, a workgroup of 4 wavefronts 256 rows, and a compute
 //     unit holds one workgroup (one wavefront per SIMD, up to 512 registers each).  Every K or V
@@ -10,25 +10,29 @@
 //     into LDS once per 256 rows: LDS traffic and copy instructions per matrix instruction halve.
 //     (With 32 rows per wavefront the operand reads alone take 125 bytes per clock of LDS
 //     bandwidth at the full matrix rate.)
-//   * With one wavefront per SIMD nothing else fills the matrix pipe while a wavefront does the
-//     exponentials, so the two kinds of work are issued together by the wavefront itself: the
-//     scores of tile t + 1 are formed while the coefficients of tile t are computed (two score
-//     accumulators), and the output product of tile t starts on the first key groups while the
-//     coefficients of the last group are still being computed.  Vector instructions placed
-//     between matrix instructions of the same wavefront run in their shadow.
-//   * Nothing is speculated: the output product of a tile may start before all its
-//     coefficients exist, so a coefficient that does not fit the storage type must be ruled
-//     out beforehand.  Every tile takes the checked step of flashd_mma.h: the row's top score
-//     is looked at first and the reference moves there if it lies more than
-//     LazyLimit::kMoveLog2 above it (the saturation of Sec. III-C in tile form); the look for
-//     tile t + 1 is part of the vector work of tile t.
+//   * The unit of work is a block of 32 keys.  With one wavefront per SIMD nothing else fills
+//     the matrix pipe while a wavefront does the exponentials, so the two kinds of work are
+//     issued together by the wavefront itself ("fused steps", wide_h1 / wide_h2): the scores
+//     of block b + 1 are formed while the coefficients of block b's first 16 keys are computed
+//     (two score accumulators), and the output product of block b runs while the coefficients
+//     of its last 16 keys, the update of the row state and the look at block b + 1's top scores
+//     are computed.  A few vector instructions follow each matrix instruction and run in its
+//     shadow; operand reads and copies are spread over the slots as well.
+//   * Nothing is speculated: the output product of a block starts before all its coefficients
+//     exist, so a coefficient that does not fit the storage type must be ruled out beforehand.
+//     Every block takes the checked step of flashd_mma.h: the row's top score is looked at first
+//     and the reference moves there if it lies more than LazyLimit::kMoveLog2 above it (the
+//     saturation of Sec. III-C in tile form); the fused steps hand a block whose reference has
+//     to move to the plain steps, which scale what the rows hold.
+//   * The output accumulators, the Q fragments and the matrix operands live in fixed
+//     accumulation registers that only inline assembly touches (flashd_wide_regs.h).
 //
-// Tiles on which a mask applies or a row may still be empty (the first tile, the diagonal
-// tiles of a causal mask, the tail) take a plain sequence of the same steps built from the
-// functions of flashd_mma.h.
+// Blocks on which a mask applies or a row may still be empty (the first block, the diagonal
+// blocks of a causal mask, the tail), and any block under a negative scale, take the plain
+// steps (wide_first_general / wide_second).
 //
-// Serves f16/bf16, d = 128, variants TILE and ONLINE_SOFTMAX, unsplit calls without state in
-// or out; everything else stays with the 128-row kernel (see wide_applies()).
+// Serves f16/bf16, d = 128, Lq a multiple of 256, unsplit calls without state in or out
+// (wide_applies()); everything else stays with the 128-row kernel.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
