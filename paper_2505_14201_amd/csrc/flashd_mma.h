@@ -57,6 +57,15 @@ template <> struct Mma<BF16> {
         acc[2] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 4, 5), ones, acc[2], false);
         acc[3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(v, v, 6, 7), ones, acc[3], false);
     }
+    // the same for one packed pair: acc + the two rounded coefficients (ones: a pair of ones in
+    // the storage type, kOnes, which the caller keeps in a scalar register)
+    static constexpr uint32_t kOnes = 0x3f803f80u;
+    static __device__ __forceinline__ float sum2(float a, float b, uint32_t packed, uint32_t ones,
+                                                 float acc) {
+        (void)a; (void)b;
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
+                                               __builtin_bit_cast(bf16x2, ones), acc, false);
+    }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, bf16x4));
     }
@@ -87,6 +96,12 @@ template <> struct Mma<F16> {
         (void)packed;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[0] += x[e];
+    }
+    static constexpr uint32_t kOnes = 0x3c003c00u;
+    static __device__ __forceinline__ float sum2(float a, float b, uint32_t packed, uint32_t ones,
+                                                 float acc) {
+        (void)packed; (void)ones;
+        return (acc + a) + b;
     }
     static __device__ __forceinline__ u32x2 pack4(f32x4 x) {
         return __builtin_bit_cast(u32x2, __builtin_convertvector(x, f16x4));

@@ -12,18 +12,17 @@
 //     bandwidth at the full matrix rate.)
 //   * The unit of work is a block of 32 keys.  With one wavefront per SIMD nothing else fills
 //     the matrix pipe while a wavefront does the exponentials, so the two kinds of work are
-//     issued together by the wavefront itself ("fused steps", wide_h1 / wide_h2): the scores
-//     of block b + 1 are formed while the coefficients of block b's first 16 keys are computed
-//     (two score accumulators), and the output product of block b runs while the coefficients
-//     of its last 16 keys, the update of the row state and the look at block b + 1's top scores
-//     are computed.  A few vector instructions follow each matrix instruction and run in its
-//     shadow; operand reads and copies are spread over the slots as well.
-//   * Nothing is speculated: the output product of a block starts before all its coefficients
-//     exist, so a coefficient that does not fit the storage type must be ruled out beforehand.
-//     Every block takes the checked step of flashd_mma.h: the row's top score is looked at first
-//     and the reference moves there if it lies more than LazyLimit::kMoveLog2 above it (the
-//     saturation of Sec. III-C in tile form); the fused steps hand a block whose reference has
-//     to move to the plain steps, which scale what the rows hold.
+//     issued together by the wavefront itself, and one block apart so that neither waits for
+//     the other ("fused step", wide_step): while the vector instructions form the coefficients
+//     of block b from its scores, the matrix pipe forms the scores of block b + 1 and multiplies
+//     the coefficients of block b - 1 into U.  A few vector instructions follow each matrix
+//     instruction; operand reads and copies are spread over the slots as well.
+//   * The coefficients of a block are formed speculatively against the rows' present references
+//     and used one step later, after the sum of each row's coefficients has been looked at: a
+//     sum beyond LazyLimit::kMaxPsum means a score far above the row's reference, and the block
+//     goes through the plain steps instead, which look at the row's top score first and move
+//     the reference there if it lies more than LazyLimit::kMoveLog2 above it (the saturation of
+//     Sec. III-C in tile form).  Nothing risky ever reaches U.
 //   * The output accumulators, the Q fragments and the matrix operands live in fixed
 //     accumulation registers that only inline assembly touches (flashd_wide_regs.h).
 //
@@ -54,6 +53,14 @@ template <int D> struct WideRegs {
     int vaddr[D / 32];
     LazyRow st[kWideRB];            // FLASH-D state, lazy form
 };
+
+// The lane's index within its wavefront, formed afresh (opaque to the compiler, so that what
+// is computed from it is computed where it is used).
+__device__ __forceinline__ int wide_lane_id() {
+    int l = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(l));
+    return l;
+}
 
 // K (IS_V = false) or V rows of one tile into LDS: this wavefront's 16 rows.
 template <int D, bool IS_V>
@@ -160,11 +167,9 @@ __device__ __forceinline__ void wide_read_v_n(int m, uint32_t addr) {
 }
 __device__ __forceinline__ void wide_wait_lds_n(int n) {
     switch (n) {
-        case 0: wide_wait_lds<0>(); break;
-        case 1: wide_wait_lds<1>(); break;
-        case 2: wide_wait_lds<2>(); break;
-        case 3: wide_wait_lds<3>(); break;
-        default: wide_wait_lds<4>(); break;
+#define FLASHD_CASE(N) case N: wide_wait_lds<N>(); break;
+        FLASHD_CASES16(FLASHD_CASE)
+#undef FLASHD_CASE
     }
 }
 #undef FLASHD_CASES16
@@ -235,213 +240,188 @@ __device__ __forceinline__ void wide_scale_u(int rb, float f) {
     }
 }
 
-// What the first half of a block's step leaves for the second: the coefficients of the first
-// 16 keys packed, the exponentials of the last 16, the partial sums, and per row the reference
-// used, the factor what the row held was scaled by, and whether the row was still empty.
+// What the first half of a block's plain step leaves for the second, per row: the sum of the
+// block's coefficients, the reference they were taken against, the factor what the row held was
+// scaled by, and whether the row was still empty.  (The coefficients themselves go to a
+// WidePacked.)
 struct WideCoef {
-    u32x4 bf0[kWideRB];
-    f32x8 pv1[kWideRB];
-    f32x4 ps[kWideRB];
-    float ref[kWideRB], f[kWideRB];
+    float psum[kWideRB], ref[kWideRB], f[kWideRB];
     bool empty[kWideRB];
 };
 
-// What one fused step hands to the next: the K operands of the next score product (requested
-// while the output product runs) and whether the next block can be taken by a fused step at
-// all: a row's reference (TILE) moves only if the block's top score lies more than
-// LazyLimit::kMoveLog2 above it; what the rows hold would then have to be scaled, which the
-// fused steps do not do (bail: the block goes through wide_first_general()).
-struct WideAhead {
-    bool bail;                  // wavefront-uniform
+// The coefficients of one 32-key block, rounded to the storage type, as operands of the output
+// product: g0 the first 16 keys, g1 the last 16.  A fused step forms those of its block and
+// multiplies those of the block before into U.
+struct WidePacked {
+    u32x4 g0[kWideRB], g1[kWideRB];
 };
 
-__device__ __forceinline__ float wide_top_part(const f32x16& a, int part, float top) {
-    if (part == 0) {
-        top = fmaxf(a[0], a[1]);
+// How many operands ahead of their use the fused steps request them from LDS (the stream of a
+// step's operands: K 0..7 of its score product, V 0..7 of its output product, then K 0.. of the
+// next step).
+#ifndef FLASHD_WIDE_LEAD
+#define FLASHD_WIDE_LEAD 3
+#endif
+constexpr int kWideLead = FLASHD_WIDE_LEAD;
+static_assert(kWideLead >= 1 && kWideLead <= 8, "the rings hold eight operands, lgkmcnt counts to 15");
+
+// The request for the first K operands of a block on its own: a fused step expects them to be the
+// last three reads issued (a fused step leaves its successor's behind; a plain step does not).
+template <int D>
+__device__ __forceinline__ void wide_request_first_k(const uint16_t* kb, const WideRegs<D>& g) {
 #pragma unroll
-        for (int r = 2; r < 8; r += 2) top = fmaxf(fmaxf(top, a[r]), a[r + 1]);
-    } else {
-#pragma unroll
-        for (int r = 8; r < 16; r += 2) top = fmaxf(fmaxf(top, a[r]), a[r + 1]);
-    }
-    return top;
+    for (int kk = 0; kk < kWideLead; ++kk) wide_req_k<D>(kk, kb, g);
 }
 
-// The look at the top scores of a block that a fused step may take next (all keys visible, no
-// row empty, scale >= 0) and the request for its successor's K operands, on their own: used
-// where a fused step follows a plain one.
-template <typename T, int D>
-__device__ __forceinline__ void wide_look_ahead(const uint16_t* kb, const WideRegs<D>& g,
-                                                const f32x16 (&acc)[kWideRB], float c_log2,
-                                                WideAhead& ah) {
-#pragma unroll
-    for (int kk = 0; kk < 3; ++kk) wide_req_k<D>(kk, kb, g);
-    bool move = false;
-#pragma unroll
-    for (int rb = 0; rb < kWideRB; ++rb) {
-        float top = wide_top_part(acc[rb], 0, 0.0f);
-        top = wide_top_part(acc[rb], 1, top);
-        move |= pair_max(top * c_log2) - g.st[rb].R > LazyLimit<T>::kMoveLog2;
-    }
-    ah.bail = __builtin_amdgcn_ballot_w64(move) != 0;
-}
-
-// First half of a fused step (an interior block: all 32 keys visible to all rows, no row
-// empty, scale >= 0, no reference to move): the scores of the next block are formed (into
-// accn, kb: that block's K rows in LDS) while the vector instructions compute the coefficients
-// of this block's first 16 keys.  The vector work is a pipeline of its own, one key per slot:
-// after matrix instruction s come the scaling of score s + 1, the exponential of score s and
-// the summing and packing of coefficient s - 1, three instructions that do not wait for one
-// another (with one wavefront per SIMD there is nobody else to fill a wait).
-template <typename T, int D>
-__device__ __forceinline__ void wide_h1(const WideAhead& ah, const uint16_t* kb,
-                                        const uint16_t* vb, const WideRegs<D>& g,
-                                        const f32x16 (&acc)[kWideRB], f32x16 (&accn)[kWideRB],
-                                        float c_log2, WideCoef& c) {
+// A fused step, for an interior block b (all 32 keys visible to all rows, no row empty): three
+// things at once, one block apart from each other so that none waits for another,
+//   * the scores of block b + 1 (16 matrix instructions into accn; kb: its K rows in LDS),
+//   * the coefficients of block b from its scores acc, by vector instructions, speculatively
+//     against the rows' present references (cur),
+//   * PENDING: the output product of block b - 1, U <- U + P V (16 matrix instructions; prev:
+//     its coefficients, vb_prev: its V rows in LDS).
+// A few vector instructions follow each matrix instruction: a pipeline of its own, after matrix
+// instruction s come the scaling of score k + 1, the exponential of score k and the packing and
+// summing of coefficient k - 1 (k runs ahead of s in the first slots, so that the row sums are
+// ready a few slots before the end).  The operands are read from LDS into fixed registers by
+// inline assembly, one operand per two slots and each six slots ahead of its use (the four
+// wavefronts of the workgroup run in step, and reads issued together by all of them queue up
+// in front of the LDS); K operands 0..2 were requested by the step before, and this step
+// requests those of the next (kb_ahead).  The waits count the read instructions issued after
+// the wanted one (a V operand takes two).
+//
+// Nothing this step does to block b is final before its end: the coefficients are used by the
+// NEXT step, after the sum of each row's coefficients has been looked at here.  A sum beyond
+// LazyLimit::kMaxPsum (or no number at all) means a score far above the row's reference: the
+// step returns true, the row state is left as it was, and the caller takes block b through the
+// plain steps, which move the reference (the saturation of Sec. III-C in tile form).  Otherwise
+//     1/beta' = 1/beta + psum.
+// copy_hook(i), i = 0..3: called in slots 3, 11, 19, 27 (PENDING only), for the caller's
+// global->LDS copies.
+template <typename T, int D, bool PENDING, typename Hook>
+__device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb_ahead,
+                                          const uint16_t* vb_prev, WideRegs<D>& g,
+                                          const f32x16 (&acc)[kWideRB], f32x16 (&accn)[kWideRB],
+                                          float c_log2, uint32_t ones, const WidePacked& prev,
+                                          WidePacked& cur, const Hook& copy_hook) {
     static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
     constexpr int NKK = D / 16;
-    // The operands are read from LDS into fixed registers by inline assembly, one operand per
-    // two slots and each six slots ahead of its use (the four wavefronts of the workgroup run
-    // in step, and reads issued together by all of them queue up in front of the LDS while
-    // the matrix pipe waits); K operands 0..2 were requested by the step before.  The waits
-    // count the read instructions issued after the wanted one (a V operand takes two).
-    (void)ah;
-#pragma unroll
-    for (int rb = 0; rb < kWideRB; ++rb) {
-        c.ref[rb] = g.st[rb].R;
-        c.f[rb] = 1.0f;
-        c.empty[rb] = false;
-        c.ps[rb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
-    // key i of the 16: row block i & 1, score register i >> 1
-    float x[17], pe[16];
-    auto F = [&](int i) __attribute__((always_inline)) {
-        if (i < 16) x[i] = fmaf(acc[i & 1][i >> 1], c_log2, -c.ref[i & 1]);
-    };
-    auto X = [&](int i) __attribute__((always_inline)) { pe[i] = exp2_fast(x[i]); };
-    auto A = [&](int i) __attribute__((always_inline)) {
-        if (i < 0) return;
-        const int rb = i & 1, e = i >> 1;
-        c.ps[rb][e & 3] += pe[i];
-        if (e & 1) c.bf0[rb][e >> 1] = Mma<T>::pack2(pe[i - 2], pe[i]);
-    };
-    F(0);
-    __builtin_amdgcn_sched_barrier(0);
-    // slot s = 2 kk + rb
-#pragma unroll
-    for (int s = 0; s < 2 * NKK; ++s) {
-        const int kk = s >> 1, rb = s & 1;
-        if ((s & 1) == 0) wide_wait_lds_n(s < 12 ? 2 : s == 12 ? 3 : 4);
-        ws_mma<T>(rb, kk, accn[rb]);
-        // K operand 3 + s / 2 (used in slot 6 + s), then V operands 0..2 of the second half
-        if (s <= 8 && (s & 1) == 0) wide_req_k<D>(3 + (s >> 1), kb, g);
-        if (s >= 10 && (s & 1) == 0) wide_req_v<D>((s - 10) >> 1, vb, g);
-        F(s + 1);
-        X(s);
-        A(s - 1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    A(15);
-}
-
-// Second half of a fused step: the output product U <- U + P V over the block's 32 keys (vb: its
-// V rows in LDS) while the vector instructions compute the coefficients of its last 16 keys
-// (two per slot in the first eight slots: their products come in the last eight), update the
-// row state,
-//     1/beta' = 1/beta + psum,
-// and look at the top scores of the next block (accn): ah.bail.  Pipelined like wide_h1.
-// copy_hook(i), i = 0..3: called in slots 1, 5, 9, 13, for the caller's global->LDS copies.
-template <typename T, int D, typename Hook>
-__device__ __forceinline__ void wide_h2(const uint16_t* vb, const uint16_t* kb_ahead,
-                                        WideRegs<D>& g, const f32x16 (&acc)[kWideRB],
-                                        const f32x16 (&accn)[kWideRB], float c_log2, WideCoef& c,
-                                        WideAhead& ah, const Hook& copy_hook) {
-    static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
     constexpr int NDB = D / 32;
-    constexpr int NV = 2 * NDB;
-    u32x4 bf1[kWideRB];
-    // pair q of the 8: row block q >> 2, score registers 8 + 2 (q & 3) and the next
-    float x0[9], x1[9], p0[8], p1[8];
-    auto F = [&](int q) __attribute__((always_inline)) {
-        if (q >= 8) return;
-        const int rb = q >> 2, e = 8 + 2 * (q & 3);
-        x0[q] = fmaf(acc[rb][e], c_log2, -c.ref[rb]);
-        x1[q] = fmaf(acc[rb][e + 1], c_log2, -c.ref[rb]);
+    float ps[kWideRB][4];
+    float ref[kWideRB];
+#pragma unroll
+    for (int rb = 0; rb < kWideRB; ++rb) ref[rb] = g.st[rb].R;
+    // key k of the 32: row block k & 1, score register k >> 1
+    float x[33], pe[32];
+    auto F = [&](int k) __attribute__((always_inline)) {
+        if (k < 32) x[k] = fmaf(acc[k & 1][k >> 1], c_log2, -ref[k & 1]);
     };
-    auto X = [&](int q) __attribute__((always_inline)) {
-        p0[q] = exp2_fast(x0[q]);
-        p1[q] = exp2_fast(x1[q]);
+    auto X = [&](int k) __attribute__((always_inline)) {
+        if (k < 32) pe[k] = exp2_fast(x[k]);
     };
-    auto A = [&](int q) __attribute__((always_inline)) {
-        if (q < 0) return;
-        const int rb = q >> 2, e = 2 * (q & 3);
-        c.ps[rb][e & 3] += p0[q];
-        c.ps[rb][(e + 1) & 3] += p1[q];
-        bf1[rb][q & 3] = Mma<T>::pack2(p0[q], p1[q]);
+    // pair of keys j of a row block's 8: the coefficients of score registers 2 j and 2 j + 1
+    auto A = [&](int k) __attribute__((always_inline)) {        // pack
+        if (k < 0 || k >= 32) return;
+        const int rb = k & 1, e = k >> 1, j = e >> 1;
+        if (e & 1) {
+            const uint32_t w = Mma<T>::pack2(pe[k - 2], pe[k]);
+            if (j < 4) cur.g0[rb][j] = w; else cur.g1[rb][j - 4] = w;
+        }
     };
-    float top[kWideRB], t2[kWideRB], sw[kWideRB], psum[kWideRB], tot[kWideRB], inv[kWideRB];
-    float tm[kWideRB];
-    bool move[kWideRB];
+    auto B = [&](int k) __attribute__((always_inline)) {        // sum, an instruction later
+        if (k < 0 || k >= 32) return;
+        const int rb = k & 1, e = k >> 1, j = e >> 1;
+        if (e & 1) {
+            const uint32_t w = j < 4 ? cur.g0[rb][j] : cur.g1[rb][j - 4];
+            ps[rb][j & 3] = Mma<T>::sum2(pe[k - 2], pe[k], w, ones, j < 4 ? 0.0f : ps[rb][j & 3]);
+        }
+    };
+    // key k passes through the pipeline
+    auto tick = [&](int k) __attribute__((always_inline)) { F(k + 1); X(k); A(k - 1); B(k - 2); };
+    float t2[kWideRB], psum[kWideRB], tot[kWideRB], inv[kWideRB];
+    auto tail = [&](int stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rb = 0; rb < kWideRB; ++rb) {
+            if (stage == 0) t2[rb] = (ps[rb][0] + ps[rb][1]) + (ps[rb][2] + ps[rb][3]);
+            if (stage == 1) psum[rb] = pair_sum(t2[rb]);
+            if (stage == 2) tot[rb] = fmaf(g.st[rb].beta, psum[rb], 1.0f);
+            if (stage == 3) inv[rb] = __builtin_amdgcn_rcpf(tot[rb]);
+        }
+    };
+    // vector work of slot s
+    auto valu = [&](int s) __attribute__((always_inline)) {
+        if (PENDING) {
+            if ((s & 7) == 3) copy_hook(s >> 3);
+            // 32 keys through slots 0..25 (two per slot in the first six), the last
+            // coefficients in slots 26 and 27, then the row sums
+            if (s < 6) { tick(2 * s); tick(2 * s + 1); }
+            else if (s < 26) tick(s + 6);
+            else if (s == 26) { A(31); B(30); }
+            else if (s == 27) B(31);
+            else tail(s - 28);
+        } else {
+            tick(2 * s);
+            tick(2 * s + 1);
+        }
+    };
     F(0);
     __builtin_amdgcn_sched_barrier(0);
-    // slot s = 2 m + rb; the products of key group m / NDB
+    // The operands of this step in the order of their use: j < 8 is K operand j, then
+    // (PENDING) V operand j - 8, then K operand j - 16 (or j - 8) of the next step.  A K operand
+    // is one read instruction, a V operand two.
+    constexpr int NOPS = PENDING ? 16 : 8;
+    auto op_size = [](int j) { return (PENDING && (j % 16) >= 8) ? 2 : 1; };
+    auto request = [&](int j) __attribute__((always_inline)) {
+        if (j < 8) wide_req_k<D>(j, kb, g);
+        else if (PENDING && j < 16) wide_req_v<D>(j - 8, vb_prev, g);
+        else wide_req_k<D>(j - NOPS, kb_ahead, g);
+    };
+    // before operand j is used: the read instructions issued after it are those of operands
+    // j + 1 .. j + kWideLead - 1
+    auto wait_for = [&](int j) __attribute__((always_inline)) {
+        int n = 0;
+        for (int i = j + 1; i < j + kWideLead; ++i) n += op_size(i);
+        wide_wait_lds_n(n);
+    };
+    // score product: slot s = 2 kk + rb
 #pragma unroll
-    for (int s = 0; s < 2 * NV; ++s) {
-        const int m = s >> 1, rb = s & 1;
-        if ((s & 1) == 0) wide_wait_lds_n(s < 12 ? 4 : s == 12 ? 3 : 2);
-        wp_mma<T>(rb, m, m / NDB == 0 ? c.bf0[rb] : bf1[rb]);
-        // V operand 3 + s / 2 (used in slot 6 + s), then the first K operands of the next step
-        if (s <= 8 && (s & 1) == 0) wide_req_v<D>(3 + (s >> 1), vb, g);
-        if (s >= 10 && (s & 1) == 0) wide_req_k<D>((s - 10) >> 1, kb_ahead, g);
-        if ((s & 3) == 1) copy_hook(s >> 2);
-        if (s < 8) { F(s + 1); X(s); A(s - 1); }
-        if (s == 8) A(7);
-        // the look at the next block: two maxima per row block and slot
-        if (s >= 8 && s < 12) {
-            const int r0 = 4 * (s - 8);
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb) {
-                if (s == 8) top[rbb] = fmaxf(accn[rbb][0], accn[rbb][1]);
-                else top[rbb] = fmaxf(fmaxf(top[rbb], accn[rbb][r0]), accn[rbb][r0 + 1]);
-                top[rbb] = fmaxf(fmaxf(top[rbb], accn[rbb][r0 + 2]), accn[rbb][r0 + 3]);
-            }
-        }
-        // sums of the coefficients, state update and the rest of the look, a stage per slot
-        if (s == 9) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb)
-                t2[rbb] = (c.ps[rbb][0] + c.ps[rbb][1]) + (c.ps[rbb][2] + c.ps[rbb][3]);
-        }
-        if (s == 10) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb) psum[rbb] = pair_sum(t2[rbb]);
-        }
-        if (s == 11) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb) tot[rbb] = fmaf(g.st[rbb].beta, psum[rbb], 1.0f);
-        }
-        if (s == 12) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb) {
-                inv[rbb] = __builtin_amdgcn_rcpf(tot[rbb]);
-                sw[rbb] = top[rbb] * c_log2;
-            }
-        }
-        if (s == 13) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb) {
-                g.st[rbb].beta *= inv[rbb];
-                tm[rbb] = pair_max(sw[rbb]);
-            }
-        }
-        if (s == 14) {
-#pragma unroll
-            for (int rbb = 0; rbb < kWideRB; ++rbb)
-                move[rbb] = tm[rbb] - g.st[rbb].R > LazyLimit<T>::kMoveLog2;
-        }
+    for (int s = 0; s < 16; ++s) {
+        const int kk = s >> 1, rb = s & 1;
+        if ((s & 1) == 0) wait_for(kk);
+        ws_mma<T>(rb, kk, accn[rb]);
+        if ((s & 1) == 0) request(kk + kWideLead);
+        valu(s);
         __builtin_amdgcn_sched_barrier(0);
     }
-    ah.bail = __builtin_amdgcn_ballot_w64(move[0] | move[1]) != 0;
+    // output product of the block before: slot 16 + q, q = 2 m + rb, key group m / NDB
+    if (PENDING) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int m = q >> 1, rb = q & 1;
+            if ((q & 1) == 0) wait_for(8 + m);
+            wp_mma<T>(rb, m, m / NDB == 0 ? prev.g0[rb] : prev.g1[rb]);
+            if ((q & 1) == 0) request(8 + m + kWideLead);
+            valu(16 + q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (!PENDING) {
+        A(31);
+        B(30);
+        B(31);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) tail(st);
+        // the scores just formed are read by vector instructions next
+        mma_fence(accn);
+    }
+    const bool bad = !(psum[0] <= LazyLimit<T>::kMaxPsum) || !(psum[1] <= LazyLimit<T>::kMaxPsum);
+    const bool risky = __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (!risky) {
+#pragma unroll
+        for (int rb = 0; rb < kWideRB; ++rb) g.st[rb].beta *= inv[rb];
+    }
+    (void)NKK;
+    return risky;
 }
 
 // First half of the step of any other block (a mask applies, rows may be empty, any scale, or
@@ -451,10 +431,10 @@ __device__ __forceinline__ void wide_h2(const uint16_t* vb, const uint16_t* kb_a
 // then at most 1, and what the row holds is scaled by f = 2^{R - m} (here).  jb: index of the
 // key in accumulator register 0 for this lane.
 template <typename T, int D>
-__device__ __forceinline__ void wide_first_general(const uint16_t* vb, WideRegs<D>& g,
-                                                   const f32x16 (&acc)[kWideRB],
+__device__ __forceinline__ void wide_first_general(WideRegs<D>& g, const f32x16 (&acc)[kWideRB],
                                                    float c_log2, int jb,
-                                                   const int (&nvis)[kWideRB], WideCoef& c) {
+                                                   const int (&nvis)[kWideRB], WideCoef& c,
+                                                   WidePacked& out) {
     const float ninf = -__builtin_inff();
 #pragma unroll
     for (int rb = 0; rb < kWideRB; ++rb) {
@@ -469,61 +449,71 @@ __device__ __forceinline__ void wide_first_general(const uint16_t* vb, WideRegs<
         if (__builtin_amdgcn_ballot_w64(c.f[rb] != 1.0f) != 0) wide_scale_u<D>(rb, c.f[rb]);
         int nv = nvis[rb];
         asm volatile("" : "+v"(nv));      // keep these compares apart from row_top_score's
-        f32x8 pv0;
+        f32x4 ps = {0.0f, 0.0f, 0.0f, 0.0f};
+        // 16 keys at a time, packed as they are formed
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float x = fmaf(acc[rb][e], c_log2, -c.ref[rb]);
-            x = ((jb + 8 * (e >> 2) + (e & 3)) >= nv) ? ninf : x;
-            const float pe = exp2_fast(x);
-            if (e < 8) pv0[e] = pe; else c.pv1[rb][e - 8] = pe;
+        for (int h = 0; h < 2; ++h) {
+            f32x8 pv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int r = 8 * h + e;
+                float x = fmaf(acc[rb][r], c_log2, -c.ref[rb]);
+                x = ((jb + 8 * (r >> 2) + (r & 3)) >= nv) ? ninf : x;
+                pv[e] = exp2_fast(x);
+                ps[e & 3] += pv[e];
+            }
+            if (h == 0) out.g0[rb] = Mma<T>::pack8(pv); else out.g1[rb] = Mma<T>::pack8(pv);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        c.bf0[rb] = Mma<T>::pack8(pv0);
-        c.ps[rb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) c.ps[rb][e & 3] += pv0[e];
+        c.psum[rb] = pair_sum((ps[0] + ps[1]) + (ps[2] + ps[3]));
     }
-    (void)vb;
 }
 
-// Second half of a block's step by plain steps: the output product U <- U + P V over the
-// block's 32 keys (vb: its V rows in LDS) for both row blocks, and the update of the row state,
-//     1/beta' = f / beta + psum   (the carried sum of coefficients, against the reference used).
+// The output product of a block on its own, U <- U + P V over the block's 32 keys (vb: its V
+// rows in LDS; b0, b1: the coefficients of its first and last 16 keys, packed).
 template <typename T, int D>
-__device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, WideCoef& c) {
+__device__ __forceinline__ void wide_pv(const uint16_t* vb, const WideRegs<D>& g,
+                                        const u32x4 (&b0)[kWideRB], const u32x4 (&b1)[kWideRB]) {
     constexpr int NDB = D / 32;
     constexpr int NV = 2 * NDB;
 #pragma unroll
     for (int m = 0; m < NV; ++m) wide_req_v<D>(m, vb, g);
-    u32x4 bf1[kWideRB];
+    wide_wait_lds<0>();
+    // the coefficients may have been packed by vector instructions just now: two wait states
+    // before the first matrix instruction reads them
+    asm volatile("s_nop 1");
+#pragma unroll
+    for (int m = 0; m < NV; ++m)
+#pragma unroll
+        for (int rb = 0; rb < kWideRB; ++rb) wp_mma<T>(rb, m, m / NDB == 0 ? b0[rb] : b1[rb]);
+}
+
+// Second half of a block's step by plain steps: the update of the row state,
+//     1/beta' = f / beta + psum   (the carried sum of coefficients, against the reference used),
+// and the output product.
+template <typename T, int D>
+__device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, const WideCoef& c,
+                                            const WidePacked& pk) {
 #pragma unroll
     for (int rb = 0; rb < kWideRB; ++rb) {
-        bf1[rb] = Mma<T>::pack8(c.pv1[rb]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) c.ps[rb][e & 3] += c.pv1[rb][e];
-        const float psum = pair_sum((c.ps[rb][0] + c.ps[rb][1]) + (c.ps[rb][2] + c.ps[rb][3]));
         const float carried = c.empty[rb] ? 0.0f : c.f[rb] * __builtin_amdgcn_rcpf(g.st[rb].beta);
-        const float tot = carried + psum;
+        const float tot = carried + c.psum[rb];
         const bool has = tot > 0.0f;        // false only for an empty row that sees no key here
         g.st[rb].beta = has ? __builtin_amdgcn_rcpf(tot) : g.st[rb].beta;
         g.st[rb].R = has ? c.ref[rb] : g.st[rb].R;
         g.st[rb].one = has ? 1.0f : g.st[rb].one;
     }
-    wide_wait_lds<0>();
-    // the coefficients were packed by vector instructions just now: two wait states before the
-    // first matrix instruction reads them
-    asm volatile("s_nop 1");
-#pragma unroll
-    for (int m = 0; m < NV; ++m)
-#pragma unroll
-        for (int rb = 0; rb < kWideRB; ++rb) wp_mma<T>(rb, m, m / NDB == 0 ? c.bf0[rb] : bf1[rb]);
+    wide_pv<T, D>(vb, g, pk.g0, pk.g1);
 }
 
-// LDS: four K slots and three V slots.  A wavefront forms the scores of block b + 1 while it
-// works on block b, so during the period of tile t it reads K(t), K(t + 1) and V(t); the
-// copies of K(t + 3) and V(t + 2) are started in that period and those started one period
-// earlier, K(t + 2) and V(t + 1), are waited for at its end: a copy has two periods to land
-// (a period of this kernel is half as long as one of the 128-row kernel, and one period is less
-// than the latency of a copy).  One workgroup barrier per tile.
+// LDS: four K slots and four V slots, tile t in slot t % 4 of each.  In the period of tile t a
+// wavefront forms the scores of the tile's second half and of the first half of tile t + 1, and
+// the output products of the second half of tile t - 1 and the first half of tile t: it reads
+// K(t), K(t + 1), V(t - 1) and V(t).  The copies of K(t + 3) and V(t + 2) are started in that
+// period and those started one period earlier, K(t + 2) and V(t + 1), are waited for at its
+// end: a copy has two periods to land (a period of this kernel is half as long as one of the
+// 128-row kernel, and one period is less than the latency of a copy).  One workgroup barrier
+// per tile.
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(kNW * 64, 1)
 void wide_kernel(Problem p, TileSched sc) {
@@ -531,7 +521,7 @@ void wide_kernel(Problem p, TileSched sc) {
     constexpr int NKK = D / 16;
     constexpr int NDB = D / 32;
     constexpr int kTile = kBC * D;
-    __shared__ __align__(1024) uint16_t lds[7 * kTile];       // K0 K1 K2 K3 V0 V1 V2
+    __shared__ __align__(1024) uint16_t lds[8 * kTile];       // K0 K1 K2 K3 V0 V1 V2 V3
     uint16_t* const vs0 = lds + 4 * kTile;
 
     const int tid = threadIdx.x;
@@ -541,6 +531,10 @@ void wide_kernel(Problem p, TileSched sc) {
     const int hh = lane >> 5;
     const DmaLane<D> dl(wave, lane);
     const float c_log2 = p.scale * kLog2e;
+    // a pair of ones in the storage type, kept in a scalar register (not a literal in each of
+    // the instructions that sum coefficients)
+    uint32_t ones = Mma<T>::kOnes;
+    asm volatile("" : "+s"(ones));
     WideRegs<D> g;
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) g.kaddr[kk] = col * D + 8 * ((2 * kk + hh) ^ C::swz_k(col));
@@ -574,15 +568,18 @@ void wide_kernel(Problem p, TileSched sc) {
         int nvis[kWideRB];
         u32x4 qload[kWideRB][NKK];
         wide_zero_u();
+        // (the lane index afresh, here and in the epilogue: what is formed from it then does
+        // not sit in registers across the tile loop)
+        const int lane_q = wide_lane_id();
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) {
-            const int row = cur.wrow0 + 32 * rb + col;
+            const int row = cur.wrow0 + 32 * rb + (lane_q & 31);
             nvis[rb] = visible_count(p, row);
             const int qr = min(row, p.Lq - 1);
 #pragma unroll
             for (int kk = 0; kk < NKK; ++kk)
-                qload[rb][kk] =
-                    *reinterpret_cast<const u32x4*>(cur.qg + (size_t)qr * D + 16 * kk + 8 * hh);
+                qload[rb][kk] = *reinterpret_cast<const u32x4*>(cur.qg + (size_t)qr * D + 16 * kk +
+                                                                8 * (lane_q >> 5));
             g.st[rb] = {0.0f, 1.0f, 0.0f, 0.0f};
         }
         // 32-key blocks this wavefront takes part in: those that start before its rows' last
@@ -597,101 +594,146 @@ void wide_kernel(Problem p, TileSched sc) {
             for (int kk = 0; kk < NKK; ++kk) wide_set_q_n(8 * rb + kk, qload[rb][kk]);
 
         f32x16 acc[2][kWideRB];          // scores of block b live in acc[b % 2]
+        WidePacked pk[2];                // coefficients of block b (a fused step's) in pk[b % 2]
         if (nbw > 0) wide_scores<T, D>(lds, g, acc[0]);
 
-        // Block b = 2 t + KB of the row tile by plain steps: K rows in kcur (KB = 0: the scores
-        // of the tile's second half come next) or knext's first half comes next.
-        auto step = [&](auto kbc, int t, const uint16_t* kcur, const uint16_t* knext,
-                        const uint16_t* vcur) __attribute__((always_inline)) {
-            constexpr int KB = decltype(kbc)::value;
-            const int b = 2 * t + KB;
-            if (b >= nbw) return;
-            const int j0 = cur.jbase + b * kWideKB;
-            const uint16_t* kn = KB == 0 ? kcur + kWideKB * D : knext;
-            const uint16_t* vb = vcur + KB * kWideKB * D;
-            if (b + 1 < nbw) wide_scores<T, D>(kn, g, acc[KB ^ 1]);
-            WideCoef c;
-            wide_first_general<T, D>(vb, g, acc[KB], c_log2, j0 + 4 * hh, nvis, c);
-            wide_second<T, D>(vb, g, c);
-        };
         // The last block a fused step can take: every key visible to every row of the
         // wavefront, and a block after it whose scores it forms.  (Block 0 never: rows are
         // still empty.)
         const int b_fused = c_log2 >= 0.0f
                                 ? min((cur.wmin - cur.jbase) / kWideKB - 1, nbw - 2) : -1;
-        WideAhead ah;
-        bool have_ah = false;       // ah belongs to the first block of the coming period
-        // Period t: start the copies of K(t + 3) and V(t + 2) into the slots of K(t - 1) and
-        // V(t - 1), which were last read in period t - 1; the two blocks of tile t; wait for
-        // the copies started in period t - 1 (all but this period's); barrier.
-        int vslot = 0;                      // t % 3
-        for (int t = 0; t < n; ++t) {
-            const int vslot1 = vslot == 2 ? 0 : vslot + 1;
-            const int vslot2 = vslot1 == 2 ? 0 : vslot1 + 1;
-            const int j0 = cur.jbase + t * kBC;
-            // this period's copies: K(t + 3) and V(t + 2).  A fused period issues them one at
-            // a time from its output-product slots, K from the first block's, V from the
-            // second's; whatever has not gone out that way goes out in one piece after the blocks.
-            const bool kcopy = t + 3 < n, vcopy = t + 2 < n;
-            // (one at a time only for tiles that lie wholly inside the keys)
-            const bool kspread = kcopy && j0 + 4 * kBC <= p.Lk;
-            const bool vspread = vcopy && j0 + 3 * kBC <= p.Lk;
-            bool kdone = false, vdone = false;
-            uint16_t* const kdst = lds + ((t + 3) & 3) * kTile;
-            uint16_t* const vdst = vs0 + vslot2 * kTile;
-            auto khook = [&](int i) __attribute__((always_inline)) {
-                switch (i) {
-                    case 0: wide_copy_one<D, false, 0>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
-                    case 1: wide_copy_one<D, false, 1>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
-                    case 2: wide_copy_one<D, false, 2>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
-                    default: wide_copy_one<D, false, 3>(cur.kg, j0 + 3 * kBC, dl, wave, kdst); break;
-                }
-            };
-            auto vhook = [&](int i) __attribute__((always_inline)) {
-                switch (i) {
-                    case 0: wide_copy_one<D, true, 0>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
-                    case 1: wide_copy_one<D, true, 1>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
-                    case 2: wide_copy_one<D, true, 2>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
-                    default: wide_copy_one<D, true, 3>(cur.vg, j0 + 2 * kBC, dl, wave, vdst); break;
-                }
-            };
-            auto nohook = [](int) __attribute__((always_inline)) {};
-            const uint16_t* kcur = lds + (t & 3) * kTile;
-            const uint16_t* knext = lds + ((t + 1) & 3) * kTile;
-            const uint16_t* vcur = vs0 + vslot * kTile;
-            bool done = false;
-            if (__builtin_expect(t >= 1 && 2 * t + 1 <= b_fused, 1)) {
-                if (!have_ah) wide_look_ahead<T, D>(kcur + kWideKB * D, g, acc[0], c_log2, ah);
-                if (__builtin_expect(!ah.bail, 1)) {
-                    WideCoef c;
-                    wide_h1<T, D>(ah, kcur + kWideKB * D, vcur, g, acc[0], acc[1], c_log2, c);
-                    if (kspread) wide_h2<T, D>(vcur, knext, g, acc[0], acc[1], c_log2, c, ah, khook);
-                    else wide_h2<T, D>(vcur, knext, g, acc[0], acc[1], c_log2, c, ah, nohook);
-                    kdone = kspread;
-                    if (__builtin_expect(!ah.bail, 1)) {
-                        wide_h1<T, D>(ah, knext, vcur + kWideKB * D, g, acc[1], acc[0], c_log2, c);
-                        if (vspread)
-                            wide_h2<T, D>(vcur + kWideKB * D, knext + kWideKB * D, g, acc[1], acc[0],
-                                          c_log2, c, ah, vhook);
-                        else
-                            wide_h2<T, D>(vcur + kWideKB * D, knext + kWideKB * D, g, acc[1], acc[0],
-                                          c_log2, c, ah, nohook);
-                        vdone = vspread;
-                        have_ah = true;
-                    } else {
-                        step(IntC<1>{}, t, kcur, knext, vcur);
-                        have_ah = false;
+        bool pending = false;       // the output product of the block before is still to come
+        bool k_ahead = false;       // K operands 0..2 of the next score product are on their way
+        // Tile t sits in K slot t % 4 and V slot t % 4.  Period t: start the copies of K(t + 3)
+        // and V(t + 2) into the slots of K(t - 1) and V(t - 2), which were last read in period
+        // t - 1; the two blocks of tile t; wait for the copies started in period t - 1 (all but
+        // this period's); barrier.
+        int t = 0;
+        auto kslot = [&](int i) __attribute__((always_inline)) { return lds + ((t + i) & 3) * kTile; };
+        auto vslot = [&](int i) __attribute__((always_inline)) { return vs0 + ((t + i) & 3) * kTile; };
+        auto khook = [&](int i) __attribute__((always_inline)) {
+            const int j3 = cur.jbase + (t + 3) * kBC;
+            switch (i) {
+                case 0: wide_copy_one<D, false, 0>(cur.kg, j3, dl, wave, kslot(3)); break;
+                case 1: wide_copy_one<D, false, 1>(cur.kg, j3, dl, wave, kslot(3)); break;
+                case 2: wide_copy_one<D, false, 2>(cur.kg, j3, dl, wave, kslot(3)); break;
+                default: wide_copy_one<D, false, 3>(cur.kg, j3, dl, wave, kslot(3)); break;
+            }
+        };
+        auto vhook = [&](int i) __attribute__((always_inline)) {
+            const int j2 = cur.jbase + (t + 2) * kBC;
+            switch (i) {
+                case 0: wide_copy_one<D, true, 0>(cur.vg, j2, dl, wave, vslot(2)); break;
+                case 1: wide_copy_one<D, true, 1>(cur.vg, j2, dl, wave, vslot(2)); break;
+                case 2: wide_copy_one<D, true, 2>(cur.vg, j2, dl, wave, vslot(2)); break;
+                default: wide_copy_one<D, true, 3>(cur.vg, j2, dl, wave, vslot(2)); break;
+            }
+        };
+        auto nohook = [](int) __attribute__((always_inline)) {};
+        // The last period both of whose blocks fused steps can take while its copies (both
+        // there, both of tiles that lie wholly inside the keys) go out one at a time.
+        const int t_hi = min(min((b_fused - 1) >> 1, n - 4), (p.Lk - cur.jbase) / kBC - 4);
+        // 0: nothing of period t is done; 1: a fused step found block 2 t risky (the scores of
+        // the next block are there, the K copies are out); 2: the same for block 2 t + 1 (both
+        // copies are out)
+        int resume = 0;
+        while (t < n) {
+            // ---- the common case as a loop of its own: periods both of whose blocks are
+            // taken by fused steps that find nothing risky
+            if (pending) {
+                while (t <= t_hi) {
+                    if (__builtin_expect(wide_step<T, D, true>(kslot(0) + kWideKB * D, kslot(1),
+                                                               vslot(3) + kWideKB * D, g, acc[0],
+                                                               acc[1], c_log2, ones, pk[1], pk[0],
+                                                               khook), 0)) {
+                        resume = 1;
+                        break;
                     }
-                    done = true;
+                    if (__builtin_expect(wide_step<T, D, true>(kslot(1), kslot(1) + kWideKB * D,
+                                                               vslot(0), g, acc[1], acc[0], c_log2,
+                                                               ones, pk[0], pk[1], vhook), 0)) {
+                        resume = 2;
+                        break;
+                    }
+                    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);       // vmcnt(8)
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    ++t;
                 }
+                if (t >= n) break;
             }
-            if (__builtin_expect(!done, 0)) {
-                step(IntC<0>{}, t, kcur, knext, vcur);
-                step(IntC<1>{}, t, kcur, knext, vcur);
-                have_ah = false;
+            // ---- any other period
+            const int j0 = cur.jbase + t * kBC;
+            // this period's copies: K(t + 3) and V(t + 2), in one piece after the blocks
+            const bool kcopy = t + 3 < n, vcopy = t + 2 < n;
+            const uint16_t* kcur = kslot(0);
+            const uint16_t* knext = kslot(1);
+            const uint16_t* vcur = vslot(0);
+            const uint16_t* vprev = vslot(3);
+            // Block b = 2 t + KB by plain steps (have_next: the scores of block b + 1 are there
+            // already, a fused step that found block b risky has formed them).
+            auto plain = [&](auto kbc, bool have_next) __attribute__((always_inline)) {
+                constexpr int KB = decltype(kbc)::value;
+                const int b = 2 * t + KB;
+                const uint16_t* kn = KB == 0 ? kcur + kWideKB * D : knext;
+                const uint16_t* vb = vcur + KB * kWideKB * D;
+                const int jb = cur.jbase + b * kWideKB;
+                if (!have_next && b + 1 < nbw) wide_scores<T, D>(kn, g, acc[KB ^ 1]);
+                WideCoef c;
+                wide_first_general<T, D>(g, acc[KB], c_log2, jb + 4 * hh, nvis, c, pk[KB]);
+                wide_second<T, D>(vb, g, c, pk[KB]);
+                k_ahead = false;
+            };
+            // Block b = 2 t + KB of the row tile.  K rows of block b + 1 in kn, of block b + 2
+            // in ka; V rows of block b - 1 in vp.
+            auto block = [&](auto kbc) __attribute__((always_inline)) {
+                constexpr int KB = decltype(kbc)::value;
+                const int b = 2 * t + KB;
+                if (b >= nbw) return;
+                const uint16_t* kn = KB == 0 ? kcur + kWideKB * D : knext;
+                const uint16_t* ka = KB == 0 ? knext : knext + kWideKB * D;
+                const uint16_t* vp = KB == 0 ? vprev + kWideKB * D : vcur;
+                bool have_next = false;
+                if (b >= 1 && b <= b_fused) {
+                    bool risky;
+                    if (pending) {
+                        risky = wide_step<T, D, true>(kn, ka, vp, g, acc[KB], acc[KB ^ 1], c_log2,
+                                                      ones, pk[KB ^ 1], pk[KB], nohook);
+                    } else {
+                        if (!k_ahead) wide_request_first_k<D>(kn, g);
+                        risky = wide_step<T, D, false>(kn, ka, vp, g, acc[KB], acc[KB ^ 1], c_log2,
+                                                       ones, pk[KB ^ 1], pk[KB], nohook);
+                    }
+                    k_ahead = true;
+                    have_next = true;
+                    pending = !risky;
+                    if (!risky) return;
+                } else if (pending) {
+                    wide_pv<T, D>(vp, g, pk[KB ^ 1].g0, pk[KB ^ 1].g1);
+                    pending = false;
+                }
+                plain(kbc, have_next);
+            };
+            bool kdone = false, vdone = false;
+            if (resume == 1) {
+                pending = false;
+                plain(IntC<0>{}, true);
+                block(IntC<1>{});
+                kdone = true;
+            } else if (resume == 2) {
+                pending = false;
+                plain(IntC<1>{}, true);
+                kdone = vdone = true;
+            } else {
+                block(IntC<0>{});
+                block(IntC<1>{});
             }
-            if (kcopy && !kdone) wide_copy<D, false>(cur.kg, j0 + 3 * kBC, p.Lk, dl, wave, lane, kdst);
-            if (vcopy && !vdone) wide_copy<D, true>(cur.vg, j0 + 2 * kBC, p.Lk, dl, wave, lane, vdst);
+            resume = 0;
+            if (kcopy && !kdone)
+                wide_copy<D, false>(cur.kg, j0 + 3 * kBC, p.Lk, dl, wave, lane, lds + ((t + 3) & 3) * kTile);
+            if (vcopy && !vdone)
+                wide_copy<D, true>(cur.vg, j0 + 2 * kBC, p.Lk, dl, wave, lane, vs0 + ((t + 2) & 3) * kTile);
             const int started = (kcopy ? 4 : 0) + (vcopy ? 4 : 0);   // copy instructions of this period
             static_assert(DmaLane<D>::NI == 4, "the waits below count 4 copies per tile and tensor");
             if (started == 8) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);       // vmcnt(8)
@@ -701,25 +743,28 @@ void wide_kernel(Problem p, TileSched sc) {
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            vslot = vslot1;
+            ++t;
         }
+        // (the wavefront's last block is never a fused step's, so nothing is pending here)
 
         // ---- epilogue: o = beta U (FLASH-D) or U / l (Alg. 2), staged through LDS so that the
         // global stores are 16 bytes per lane and whole rows are contiguous.  Every wavefront
         // is past the last barrier, so all of LDS is free; a wavefront stages its 64 rows in
         // its own 64 x D elements.  Chunk c of row r sits at chunk position c ^ (r % CPR).
         uint16_t* stage = lds + wave * (64 * D);
+        const int lane_e = wide_lane_id();
+        const int col_e = lane_e & 31, hh_e = lane_e >> 5;
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) {
             float fin = g.st[rb].beta;
             fin *= p.oscale;
-            const int srow = 32 * rb + col;
+            const int srow = 32 * rb + col_e;
 #pragma unroll
             for (int i = 0; i < NDB; ++i) {
                 const f32x16 u = wide_get_u_n(4 * rb + i);
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
-                    const int dc = 32 * i + 8 * gq + 4 * hh;
+                    const int dc = 32 * i + 8 * gq + 4 * hh_e;
                     f32x4 x4;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x4[e] = u[4 * gq + e] * fin;
@@ -738,7 +783,7 @@ void wide_kernel(Problem p, TileSched sc) {
             u32x4 xs[8];
 #pragma unroll
             for (int n8 = 0; n8 < 8; ++n8) {
-                const int slot = (h + n8) * 64 + lane;
+                const int slot = (h + n8) * 64 + lane_e;
                 const int r = slot / C::CPR;
                 const int c = slot % C::CPR;
                 xs[n8] = *reinterpret_cast<const u32x4*>(stage + r * D + 8 * (c ^ (r % C::CPR)));
@@ -746,7 +791,7 @@ void wide_kernel(Problem p, TileSched sc) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int n8 = 0; n8 < 8; ++n8) {
-                const int slot = (h + n8) * 64 + lane;
+                const int slot = (h + n8) * 64 + lane_e;
                 const int r = slot / C::CPR;
                 const int c = slot % C::CPR;
                 if (cur.wrow0 + r < p.Lq)
