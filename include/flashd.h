@@ -84,9 +84,9 @@ typedef enum {
                                           interleaved by hand) where it can serve the call:
                                           f16/bf16, d = 128, Lq a multiple of 256, no splits,
                                           no state; any other call runs as TILE.  Same
-                                          arithmetic; measured about level with TILE on long
-                                          unmasked inputs and slower under a causal mask, so
-                                          it is never chosen automatically                  */
+                                          arithmetic; measured a few percent ahead of TILE
+                                          on long inputs and behind it on short causal
+                                          ones; never chosen automatically                  */
 } flashd_variant;
 
 /*
