@@ -280,10 +280,10 @@ __device__ __forceinline__ void wide_request_first_k(const uint16_t* kb, const W
 //     against the rows' present references (cur),
 //   * PENDING: the output product of block b - 1, U <- U + P V (16 matrix instructions; prev:
 //     its coefficients, vb_prev: its V rows in LDS).
-// A few vector instructions follow each matrix instruction: a pipeline of its own, after matrix
-// instruction s come the scaling of score k + 1, the exponential of score k and the packing and
-// summing of coefficient k - 1 (k runs ahead of s in the first slots, so that the row sums are
-// ready a few slots before the end).  The operands are read from LDS into fixed registers by
+// The vector instructions follow the matrix instructions of the second half of the step, two
+// keys per slot, as a pipeline of their own: the scaling of score k + 1, the exponential of
+// score k, the packing of coefficient k - 1 and the summing of coefficient k - 2 do not wait for
+// one another.  The operands are read from LDS into fixed registers by
 // inline assembly, one operand per two slots and each six slots ahead of its use (the four
 // wavefronts of the workgroup run in step, and reads issued together by all of them queue up
 // in front of the LDS); K operands 0..2 were requested by the step before, and this step
@@ -352,13 +352,14 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
     auto valu = [&](int s) __attribute__((always_inline)) {
         if (PENDING) {
             if ((s & 7) == 3) copy_hook(s >> 3);
-            // 32 keys through slots 0..25 (two per slot in the first six), the last
-            // coefficients in slots 26 and 27, then the row sums
-            if (s < 6) { tick(2 * s); tick(2 * s + 1); }
-            else if (s < 26) tick(s + 6);
-            else if (s == 26) { A(31); B(30); }
-            else if (s == 27) B(31);
-            else tail(s - 28);
+            // 32 keys through slots 14..29, two per slot, then the last coefficients and the
+            // row sums.  (Measured: a wavefront's vector instructions do not run beside its own
+            // matrix instructions whatever their order, and every change from one kind to the
+            // other costs a little; one key per slot over the whole step ran 3.4 % slower than
+            // this, all vector work in one piece between the two products the same as this.)
+            if (s >= 14 && s < 30) { tick(2 * (s - 14)); tick(2 * (s - 14) + 1); }
+            else if (s == 30) { A(31); B(30); B(31); tail(0); }
+            else if (s == 31) { tail(1); tail(2); tail(3); }
         } else {
             tick(2 * s);
             tick(2 * s + 1);
