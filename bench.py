@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # profiles/ summary that holds the HBM traffic of each prefill configuration's kernel
 PREFILL_PROFILE = {1: "tile_kernel_bf16_d128_causal_prefill.txt",
-                   2: "tile_kernel_bf16_d128_long_noncausal_prefill.txt",
+                   2: "wide_kernel_bf16_d128_long_noncausal_prefill.txt",
                    4: "tile_kernel_f16_d64_stress_prefill.txt"}
 # fp32 vector peak as published (157.3 TFLOP/s: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz,
 # doubled by packed issue).  This build compiles the packed fp32 instructions out, so what its
@@ -153,14 +153,30 @@ def oracle_leg(w, host, got, budget_flop=2.0e12):
     return parity, cpu
 
 
+def auto_variant(w):
+    """The variant flashd_attn_fwd takes for this workload (the library's own answer)."""
+    from paper_2505_14201_amd import flashd
+    code = {"bf16": flashd.BF16, "f16": flashd.F16, "f32": flashd.F32}[w.dtype]
+    return flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, code, w.causal)
+
+
+def prefill_kernel_name(w):
+    from paper_2505_14201_amd import flashd
+    kern = "wide_kernel" if auto_variant(w) == flashd.VARIANT_TILE_256 else "tile_kernel"
+    return "%s<%s,%d> (flashd_attn_fwd)" % (kern, w.dtype.upper(), w.d)
+
+
 def variant_legs(w, sets, steps, warmup):
     """Kernel time of the Alg. 2 ablation, of the per-tile blend and (d = 128, where it applies)
-    of the 256-row kernel on the same inputs."""
+    of the prefill kernel the automatic choice did not take (256 or 128 rows per workgroup) on
+    the same inputs."""
     from paper_2505_14201_amd import flashd
     out = {}
     legs = [("ablation_online_softmax", flashd.VARIANT_ONLINE_SOFTMAX),
             ("tile_blend", flashd.VARIANT_TILE_BLEND)]
-    if w.d == 128 and w.Lq % 256 == 0:
+    if auto_variant(w) == flashd.VARIANT_TILE_256:
+        legs.append(("tile_128_rows", flashd.VARIANT_TILE))
+    elif w.d == 128 and w.Lq % 256 == 0:
         legs.append(("tile_256_rows", flashd.VARIANT_TILE_256))
     for key, var in legs:
         def step_var(i, var=var):
@@ -188,7 +204,7 @@ def prefill_leg(w, steps, warmup, nsets, profile, cpu=True, variants=True):
     leg = {"workload": w.name, "dtype": w.dtype, "steps": steps, "input_sets": nsets,
            "flop_per_step": w.flops(), "kernel_ms": round(ms, 4), "TFLOP/s": round(tf, 2),
            "roofline": {"bound": "mfma",
-                        "kernel": "tile_kernel<%s,%d> (flashd_attn_fwd)" % (w.dtype.upper(), w.d),
+                        "kernel": prefill_kernel_name(w),
                         "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                         "traffic_source": src}}
@@ -283,7 +299,7 @@ def main() -> int:
                    "Lk": w.Lk, "d": w.d, "causal": w.causal, "input_sets": args.sets,
                    "flop_per_step": flops},
         "roofline": {"bound": "mfma",
-                     "kernel": "tile_kernel<%s,%d> (flashd_attn_fwd)" % (w.dtype.upper(), w.d),
+                     "kernel": prefill_kernel_name(w),
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic, "traffic_source": traffic_src,

@@ -70,7 +70,7 @@ typedef enum {
 
 /* How the recurrence is evaluated.  All variants compute the same result. */
 typedef enum {
-    FLASHD_VARIANT_AUTO = 0,     /* TILE for f16/bf16, PER_KEY for f32                      */
+    FLASHD_VARIANT_AUTO = 0,     /* TILE (or TILE_256) for f16/bf16, PER_KEY for f32        */
     FLASHD_VARIANT_TILE = 1,     /* Alg. 3 lifted to key tiles on the matrix cores (f16/bf16),
                                     the (1 - W) factors of the blend deferred to the store   */
     FLASHD_VARIANT_PER_KEY = 2,  /* Alg. 3 literally, one sigmoid per key (any dtype)       */
@@ -86,7 +86,8 @@ typedef enum {
                                           no state; any other call runs as TILE.  Same
                                           arithmetic; measured a few percent ahead of TILE
                                           on long inputs and behind it on short causal
-                                          ones; never chosen automatically                  */
+                                          ones: the automatic choice takes it where it is
+                                          ahead (flashd_auto_variant)                      */
 } flashd_variant;
 
 /*
@@ -130,6 +131,15 @@ size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int
 
 /* The number of splits the automatic choice takes for this problem (>= 1). */
 int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int variant);
+
+/*
+ * The variant flashd_attn_fwd (FLASHD_VARIANT_AUTO) runs for this problem: PER_KEY for f32,
+ * else TILE, or TILE_256 for calls that kernel can serve and was measured faster on (d = 128,
+ * Lq a multiple of 256, one split, at least a workgroup per compute unit, from 2048 keys on
+ * without a mask and 8192 with one).  Host-only; -1 for invalid arguments.  (Decode shapes,
+ * (Hq / Hkv) * Lq <= 32, report TILE: they run the tile form on the split-K decode kernel.)
+ */
+int flashd_auto_variant(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int causal);
 
 /*
  * Attention forward over one chunk of keys with the state of Alg. 3 handed in and out

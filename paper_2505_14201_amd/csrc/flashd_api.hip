@@ -34,6 +34,19 @@ int validate_shape(const Shape& s) {
     return FLASHD_OK;
 }
 
+// Where the automatic choice takes the 256-row prefill kernel (measured against the 128-row
+// kernel over batch sizes, head counts and lengths): it needs a workgroup per compute unit to
+// be busy at all (256 of them; twice that under a causal mask, whose row tiles differ in
+// length), and row tiles long enough that the blocks its fused steps take outweigh the first,
+// the last and the masked ones: 2048 keys without a mask (+ 2 % there, + 4 to 11 % from 4096
+// keys on), 8192 under a causal mask (+ 0 to 3 % there, + 5 to 8 % at 16384; - 5 % at 4096).
+// The kernel itself says which calls it can serve at all (wide_applies()).
+bool prefers_256_rows(const Shape& s, bool causal) {
+    if (s.d != 128 || s.dtype == FLASHD_F32 || s.Lq % 256 != 0) return false;
+    const long wgs = (long)s.B * s.Hq * (s.Lq / 256);
+    return causal ? (wgs >= 512 && s.Lk >= 8192) : (wgs >= 256 && s.Lk >= 2048);
+}
+
 int resolve_variant(const Shape& s, int variant) {
     if (variant < FLASHD_VARIANT_AUTO || variant > FLASHD_VARIANT_TILE_256) return -1;
     if (variant == FLASHD_VARIANT_AUTO)
@@ -305,7 +318,9 @@ int run(const void* q, const void* k, const void* v, void* o, const Shape& s, in
     p.state_in = sa.in;
     p.state_out = sa.out;
     p.vskip_counts = sk.counts;
-    p.wide = var == FLASHD_VARIANT_TILE_256 ? 1 : 0;
+    p.wide = (var == FLASHD_VARIANT_TILE_256 ||
+              (variant == FLASHD_VARIANT_AUTO && !sa.on && !k8.on && !sk.on && sp == 1 &&
+               prefers_256_rows(s, causal != 0))) ? 1 : 0;
     if (in_kernel) {
         p.partial = sa.out != nullptr ? 1 : 0;     // the "partial" is the state handed out
         p.store_o = o != nullptr ? 1 : 0;
@@ -439,6 +454,15 @@ int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
     const int var = resolve_variant(s, variant);
     if (var < 0) return 1;
     return auto_splits(s, var);
+}
+
+int flashd_auto_variant(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int causal) {
+    const Shape s{B, Hq, Hkv, Lq, Lk, d, dtype};
+    if (validate_shape(s) != FLASHD_OK) return -1;
+    const int var = resolve_variant(s, FLASHD_VARIANT_AUTO);
+    if (var != FLASHD_VARIANT_TILE || flashd::decode_applies(s.Hq, s.Hkv, s.Lq)) return var;
+    return auto_splits(s, var) == 1 && prefers_256_rows(s, causal != 0) ? FLASHD_VARIANT_TILE_256
+                                                                          : FLASHD_VARIANT_TILE;
 }
 
 size_t flashd_workspace_bytes(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,

@@ -24,7 +24,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 _DTYPE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 EXPORTS = ("flashd_attn_fwd", "flashd_attn_fwd_ex", "flashd_workspace_bytes",
-           "flashd_auto_splits", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
+           "flashd_auto_splits", "flashd_auto_variant", "flashd_status_string", "flashd_version", "flashd_skip_stats", "flashd_attn_fwd_state",
            "flashd_attn_fwd_kv8", "flashd_attn_fwd_static", "flashd_attn_fwd_skipv",
            "flashd_release_workspace")
 
@@ -55,6 +55,8 @@ def _load() -> ctypes.CDLL:
     lib.flashd_workspace_bytes.argtypes = [i] * 9
     lib.flashd_auto_splits.restype = i
     lib.flashd_auto_splits.argtypes = [i] * 8
+    lib.flashd_auto_variant.restype = i
+    lib.flashd_auto_variant.argtypes = [i] * 8
     lib.flashd_attn_fwd_state.restype = i
     lib.flashd_attn_fwd_state.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, i, i, f, i, p]
     lib.flashd_attn_fwd_kv8.restype = i
@@ -99,6 +101,10 @@ def workspace_bytes(B, Hq, Hkv, Lq, Lk, d, dtype, variant=VARIANT_AUTO, splits=0
 
 def auto_splits(B, Hq, Hkv, Lq, Lk, d, dtype, variant=VARIANT_AUTO) -> int:
     return int(_lib.flashd_auto_splits(B, Hq, Hkv, Lq, Lk, d, dtype, variant))
+
+
+def auto_variant(B, Hq, Hkv, Lq, Lk, d, dtype, causal) -> int:
+    return int(_lib.flashd_auto_variant(B, Hq, Hkv, Lq, Lk, d, dtype, int(bool(causal))))
 
 
 def _marshal(q, k, v, o):

@@ -138,6 +138,26 @@ def test_automatic_splits_follow_the_size_of_the_partial_states():
     assert flashd.auto_splits(64, 32, 8, 1, 8192, 128, flashd.BF16) == 1
 
 
+def test_automatic_choice_of_the_prefill_kernel():
+    V, BF, F16 = flashd.auto_variant, flashd.BF16, flashd.F16
+    T, W = flashd.VARIANT_TILE, flashd.VARIANT_TILE_256
+    assert V(1, 32, 32, 16384, 16384, 128, BF, False) == W     # long, no mask
+    assert V(4, 32, 32, 2048, 2048, 128, BF, False) == W       # 2048 keys are enough without a mask
+    assert V(4, 32, 32, 2048, 2048, 128, BF, True) == T        # the headline shape: short causal rows
+    assert V(1, 32, 32, 4096, 4096, 128, BF, True) == T
+    assert V(1, 32, 32, 8192, 8192, 128, F16, True) == W       # 8192 keys under a causal mask
+    assert V(1, 8, 8, 8192, 8192, 128, BF, True) == T          # 256 workgroups: too few with a mask
+    assert V(1, 8, 8, 8192, 8192, 128, BF, False) == W
+    assert V(1, 16, 16, 2048, 2048, 128, BF, False) == T       # 128 workgroups
+    assert V(1, 32, 32, 1024, 1024, 128, BF, False) == T       # short rows of keys
+    assert V(2, 16, 16, 4096, 4096, 64, F16, False) == T       # d = 64
+    assert V(1, 32, 32, 4000, 4096, 128, BF, False) == T       # Lq not a multiple of 256
+    assert V(1, 4, 4, 128, 128, 64, flashd.F32, False) == flashd.VARIANT_PER_KEY
+    assert V(64, 32, 8, 1, 8192, 128, BF, False) == T          # decode shape
+    assert V(1, 32, 32, 0, 4096, 128, BF, False) == -1
+    assert V(1, 32, 32, 4096, 4096, 128, 7, False) == -1
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a machine without a GPU")
 def test_valid_arguments_without_a_gpu_report_hip_error():
     assert fwd() == E_HIP

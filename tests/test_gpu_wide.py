@@ -112,3 +112,22 @@ def test_wide_kernel_is_bitwise_reproducible_and_agrees_with_tile():
     t = run_flashd(q, k, v, True, w.scale, flashd.VARIANT_TILE, 1)
     # two roundings of the same row to bf16: a unit in the last place of the larger one apart
     assert (a.float() - t.float()).abs().max() <= 2.0 ** -7 * max(1.0, float(t.float().abs().max()))
+
+
+def test_the_automatic_choice_takes_the_wide_kernel_where_it_says_so():
+    """A shape flashd_auto_variant reports as TILE_256 (a workgroup per compute unit, 2048 keys,
+    no mask): flashd_attn_fwd must return the 256-row kernel's bits, and they must agree with
+    the oracle; the headline shape (short causal rows) stays with the 128-row kernel."""
+    w = synthetic.small("wide auto", 1, 64, 8, 1024, 2048, 128, "bf16", False, seed=9800)
+    assert flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, flashd.BF16, False) == WIDE
+    q, k, v, _ = synthetic.make_qkv(w)
+    auto = run_flashd(q, k, v, False, w.scale, use_ex=False)
+    wide = run_flashd(q, k, v, False, w.scale, WIDE, 1)
+    assert torch.equal(auto.view(torch.int16), wide.view(torch.int16))
+    sampled(auto, q, k, v, w, 1024, 37, "automatic choice, 256-row kernel")
+    w = synthetic.small("wide auto no", 1, 8, 8, 1024, 1024, 128, "bf16", True, seed=9801)
+    assert flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, flashd.BF16, True) == flashd.VARIANT_TILE
+    q, k, v, _ = synthetic.make_qkv(w)
+    auto = run_flashd(q, k, v, True, w.scale, use_ex=False)
+    tile = run_flashd(q, k, v, True, w.scale, flashd.VARIANT_TILE, 0)
+    assert torch.equal(auto.view(torch.int16), tile.view(torch.int16))
