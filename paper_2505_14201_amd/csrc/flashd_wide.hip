@@ -46,12 +46,24 @@ constexpr int kWideRB = 2;                      // 32-row blocks per wavefront
 constexpr int kWideBM = 32 * kWideRB * kNW;     // query rows per workgroup
 constexpr int kWideKB = 32;                     // keys per step of a wavefront (half a tile)
 
+// A row's state in this kernel, the lazy form of flashd_mma.h with the blend factor kept as its
+// reciprocal: o = U / l, where l = 1 / beta is the sum of 2^{s_j - R} over the keys seen so far.
+// A lane holds the part of l that comes from the keys its own registers hold (the hh = 0 lane
+// of a row keys 0-3, 8-11, ... of every 16, its partner the others); the two parts are added
+// once, at the store.  Kept that way a fused step only adds the block's coefficients to l (no
+// reciprocal, no exchange between lanes per block); the quotient is formed once per row.
+struct WideRow {
+    float R;      // exponent reference, log2 units
+    float l;      // this lane's part of 1 / beta
+    float one;    // 0.0f while the row is empty, then 1.0f
+};
+
 // (The output accumulators U and the Q fragments are not here: they live in fixed accumulation
 // registers, see flashd_wide_regs.h.)
 template <int D> struct WideRegs {
     int kaddr[D / 16];
     int vaddr[D / 32];
-    LazyRow st[kWideRB];            // FLASH-D state, lazy form
+    WideRow st[kWideRB];            // FLASH-D state, lazy form
 };
 
 // The lane's index within its wavefront, formed afresh (opaque to the compiler, so that what
@@ -245,7 +257,7 @@ __device__ __forceinline__ void wide_scale_u(int rb, float f) {
 // scaled by, and whether the row was still empty.  (The coefficients themselves go to a
 // WidePacked.)
 struct WideCoef {
-    float psum[kWideRB], ref[kWideRB], f[kWideRB];
+    float psum[kWideRB], half[kWideRB], ref[kWideRB], f[kWideRB];   // half: this lane's part of psum
     bool empty[kWideRB];
 };
 
@@ -295,7 +307,8 @@ __device__ __forceinline__ void wide_request_first_k(const uint16_t* kb, const W
 // LazyLimit::kMaxPsum (or no number at all) means a score far above the row's reference: the
 // step returns true, the row state is left as it was, and the caller takes block b through the
 // plain steps, which move the reference (the saturation of Sec. III-C in tile form).  Otherwise
-//     1/beta' = 1/beta + psum.
+//     1/beta' = 1/beta + psum,
+// which costs nothing here: the coefficients are summed straight onto the rows' l = 1 / beta.
 // copy_hook(i), i = 0..3: called in slots 3, 11, 19, 27 (PENDING only), for the caller's
 // global->LDS copies.
 template <typename T, int D, bool PENDING, typename Hook>
@@ -307,10 +320,12 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
     static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
     constexpr int NKK = D / 16;
     constexpr int NDB = D / 32;
-    float ps[kWideRB][4];
-    float ref[kWideRB];
+    float ref[kWideRB], l[kWideRB];
 #pragma unroll
-    for (int rb = 0; rb < kWideRB; ++rb) ref[rb] = g.st[rb].R;
+    for (int rb = 0; rb < kWideRB; ++rb) {
+        ref[rb] = g.st[rb].R;
+        l[rb] = g.st[rb].l;
+    }
     // key k of the 32: row block k & 1, score register k >> 1
     float x[33], pe[32];
     auto F = [&](int k) __attribute__((always_inline)) {
@@ -333,21 +348,11 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
         const int rb = k & 1, e = k >> 1, j = e >> 1;
         if (e & 1) {
             const uint32_t w = j < 4 ? cur.g0[rb][j] : cur.g1[rb][j - 4];
-            ps[rb][j & 3] = Mma<T>::sum2(pe[k - 2], pe[k], w, ones, j < 4 ? 0.0f : ps[rb][j & 3]);
+            l[rb] = Mma<T>::sum2(pe[k - 2], pe[k], w, ones, l[rb]);
         }
     };
     // key k passes through the pipeline
     auto tick = [&](int k) __attribute__((always_inline)) { F(k + 1); X(k); A(k - 1); B(k - 2); };
-    float t2[kWideRB], psum[kWideRB], tot[kWideRB], inv[kWideRB];
-    auto tail = [&](int stage) __attribute__((always_inline)) {
-#pragma unroll
-        for (int rb = 0; rb < kWideRB; ++rb) {
-            if (stage == 0) t2[rb] = (ps[rb][0] + ps[rb][1]) + (ps[rb][2] + ps[rb][3]);
-            if (stage == 1) psum[rb] = pair_sum(t2[rb]);
-            if (stage == 2) tot[rb] = fmaf(g.st[rb].beta, psum[rb], 1.0f);
-            if (stage == 3) inv[rb] = __builtin_amdgcn_rcpf(tot[rb]);
-        }
-    };
     // vector work of slot s
     auto valu = [&](int s) __attribute__((always_inline)) {
         if (PENDING) {
@@ -358,8 +363,7 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
             // other costs a little; one key per slot over the whole step ran 3.4 % slower than
             // this, all vector work in one piece between the two products the same as this.)
             if (s >= 14 && s < 30) { tick(2 * (s - 14)); tick(2 * (s - 14) + 1); }
-            else if (s == 30) { A(31); B(30); B(31); tail(0); }
-            else if (s == 31) { tail(1); tail(2); tail(3); }
+            else if (s == 30) { A(31); B(30); B(31); }
         } else {
             tick(2 * s);
             tick(2 * s + 1);
@@ -410,16 +414,17 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
         A(31);
         B(30);
         B(31);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) tail(st);
         // the scores just formed are read by vector instructions next
         mma_fence(accn);
     }
-    const bool bad = !(psum[0] <= LazyLimit<T>::kMaxPsum) || !(psum[1] <= LazyLimit<T>::kMaxPsum);
+    // what the block added to this lane's part of the rows' sums: beyond the limit (or no
+    // number) if any of its coefficients was
+    const bool bad = !(l[0] - g.st[0].l <= LazyLimit<T>::kMaxPsum) ||
+                     !(l[1] - g.st[1].l <= LazyLimit<T>::kMaxPsum);
     const bool risky = __builtin_amdgcn_ballot_w64(bad) != 0;
     if (!risky) {
 #pragma unroll
-        for (int rb = 0; rb < kWideRB; ++rb) g.st[rb].beta *= inv[rb];
+        for (int rb = 0; rb < kWideRB; ++rb) g.st[rb].l = l[rb];
     }
     (void)NKK;
     return risky;
@@ -466,7 +471,8 @@ __device__ __forceinline__ void wide_first_general(WideRegs<D>& g, const f32x16 
             if (h == 0) out.g0[rb] = Mma<T>::pack8(pv); else out.g1[rb] = Mma<T>::pack8(pv);
             __builtin_amdgcn_sched_barrier(0);
         }
-        c.psum[rb] = pair_sum((ps[0] + ps[1]) + (ps[2] + ps[3]));
+        c.half[rb] = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        c.psum[rb] = pair_sum(c.half[rb]);
     }
 }
 
@@ -490,17 +496,19 @@ __device__ __forceinline__ void wide_pv(const uint16_t* vb, const WideRegs<D>& g
 }
 
 // Second half of a block's step by plain steps: the update of the row state,
-//     1/beta' = f / beta + psum   (the carried sum of coefficients, against the reference used),
+//     l' = f l + psum   (l = 1 / beta: the carried sum of coefficients, against the reference
+//                        used; each lane of a row keeps its own part),
 // and the output product.
 template <typename T, int D>
 __device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, const WideCoef& c,
                                             const WidePacked& pk) {
 #pragma unroll
     for (int rb = 0; rb < kWideRB; ++rb) {
-        const float carried = c.empty[rb] ? 0.0f : c.f[rb] * __builtin_amdgcn_rcpf(g.st[rb].beta);
-        const float tot = carried + c.psum[rb];
-        const bool has = tot > 0.0f;        // false only for an empty row that sees no key here
-        g.st[rb].beta = has ? __builtin_amdgcn_rcpf(tot) : g.st[rb].beta;
+        // false only for an empty row that sees no key here (a row that is not empty has a sum
+        // above zero against its reference, and the block's top score has coefficient 1 against
+        // a reference that moves)
+        const bool has = !c.empty[rb] || c.psum[rb] > 0.0f;
+        g.st[rb].l = has ? fmaf(c.f[rb], g.st[rb].l, c.half[rb]) : g.st[rb].l;
         g.st[rb].R = has ? c.ref[rb] : g.st[rb].R;
         g.st[rb].one = has ? 1.0f : g.st[rb].one;
     }
@@ -581,7 +589,7 @@ void wide_kernel(Problem p, TileSched sc) {
             for (int kk = 0; kk < NKK; ++kk)
                 qload[rb][kk] = *reinterpret_cast<const u32x4*>(cur.qg + (size_t)qr * D + 16 * kk +
                                                                 8 * (lane_q >> 5));
-            g.st[rb] = {0.0f, 1.0f, 0.0f, 0.0f};
+            g.st[rb] = {0.0f, 0.0f, 0.0f};
         }
         // 32-key blocks this wavefront takes part in: those that start before its rows' last
         // visible key
@@ -757,8 +765,9 @@ void wide_kernel(Problem p, TileSched sc) {
         const int col_e = lane_e & 31, hh_e = lane_e >> 5;
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) {
-            float fin = g.st[rb].beta;
-            fin *= p.oscale;
+            // beta = 1 / l, the two lanes' parts added; a row that saw no key stores zeros
+            const float lrow = pair_sum(g.st[rb].l);
+            const float fin = lrow > 0.0f ? p.oscale * __builtin_amdgcn_rcpf(lrow) : 0.0f;
             const int srow = 32 * rb + col_e;
 #pragma unroll
             for (int i = 0; i < NDB; ++i) {
