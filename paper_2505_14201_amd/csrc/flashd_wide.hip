@@ -38,8 +38,6 @@
 #include "flashd_tile_parts.h"
 #include "flashd_wide_regs.h"
 
-#include <type_traits>
-
 namespace flashd {
 
 constexpr int kWideRB = 2;                      // 32-row blocks per wavefront
@@ -212,15 +210,21 @@ __device__ __forceinline__ void mma_fence(f32x16 (&acc)[kWideRB]) {
 // together by the four wavefronts of the workgroup, which run in step, 32 of these queue up in
 // front of the one address unit), and without a branch in between.
 template <int D, bool IS_V, int N>
-__device__ __forceinline__ void wide_copy_one(const uint16_t* src, int j0, const DmaLane<D>& dl,
+__device__ __forceinline__ void wide_copy_one(const uint16_t* src, int j0, DmaLane<D>& dl,
                                               int wave, uint16_t* dst) {
     constexpr int NI = DmaLane<D>::NI;
     static_assert(N < NI, "a tile takes NI copy instructions per wavefront");
     uint16_t* w = dst + wave * (NI * 512);
     const char* t = reinterpret_cast<const char*>(src + (size_t)j0 * D);
-    uint32_t off = IS_V ? dl.voff : dl.koff[N];
-    asm volatile("" : "+v"(off));
-    __builtin_amdgcn_global_load_lds((gptr_t)(t + off), (lptr_t)w, 16, 1024 * N, 0);
+    // (the lane's offset is made opaque where it lives, not in a copy: the address stays a
+    // scalar base plus this 32-bit register, and no instruction is spent on it)
+    if (IS_V) {
+        asm volatile("" : "+v"(dl.voff));
+        __builtin_amdgcn_global_load_lds((gptr_t)(t + dl.voff), (lptr_t)w, 16, 1024 * N, 0);
+    } else {
+        asm volatile("" : "+v"(dl.koff[N]));
+        __builtin_amdgcn_global_load_lds((gptr_t)(t + dl.koff[N]), (lptr_t)w, 16, 1024 * N, 0);
+    }
 }
 
 // Raw scores of one 32-key block (kb: its rows in LDS) for both row blocks, by plain steps:
@@ -318,7 +322,6 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
                                           float c_log2, uint32_t ones, const WidePacked& prev,
                                           WidePacked& cur, const Hook& copy_hook) {
     static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
-    constexpr int NKK = D / 16;
     constexpr int NDB = D / 32;
     float ref[kWideRB], l[kWideRB];
 #pragma unroll
@@ -426,7 +429,6 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) g.st[rb].l = l[rb];
     }
-    (void)NKK;
     return risky;
 }
 
@@ -538,7 +540,7 @@ void wide_kernel(Problem p, TileSched sc) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31;
     const int hh = lane >> 5;
-    const DmaLane<D> dl(wave, lane);
+    DmaLane<D> dl(wave, lane);
     const float c_log2 = p.scale * kLog2e;
     // a pair of ones in the storage type, kept in a scalar register (not a literal in each of
     // the instructions that sum coefficients)
@@ -824,7 +826,7 @@ bool wide_applies(const Problem& p, int mode) {
 }
 
 template <typename T, int D>
-static hipError_t launch_wide_t(const Problem& p, int mode, hipStream_t st) {
+static hipError_t launch_wide_t(const Problem& p, hipStream_t st) {
     const long m_tiles = (p.Lq + kWideBM - 1) / kWideBM;
     if (m_tiles * p.B * p.Hq > 0x7fffffffL) return hipErrorInvalidValue;
     const TileSched sc = tile_sched(p, kCusPerXcd, kWideBM);
@@ -835,8 +837,8 @@ static hipError_t launch_wide_t(const Problem& p, int mode, hipStream_t st) {
 
 hipError_t launch_wide(const Problem& p, int mode, hipStream_t st) {
     if (!wide_applies(p, mode)) return hipErrorInvalidValue;
-    if (p.dtype == 1) return launch_wide_t<F16, 128>(p, mode, st);
-    return launch_wide_t<BF16, 128>(p, mode, st);
+    if (p.dtype == 1) return launch_wide_t<F16, 128>(p, st);
+    return launch_wide_t<BF16, 128>(p, st);
 }
 
 }  // namespace flashd
