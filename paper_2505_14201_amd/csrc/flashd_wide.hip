@@ -313,8 +313,9 @@ __device__ __forceinline__ void wide_request_first_k(const uint16_t* kb, const W
 // plain steps, which move the reference (the saturation of Sec. III-C in tile form).  Otherwise
 //     1/beta' = 1/beta + psum,
 // which costs nothing here: the coefficients are summed straight onto the rows' l = 1 / beta.
-// copy_hook(i), i = 0..3: called in slots 3, 11, 19, 27 (PENDING only), for the caller's
-// global->LDS copies.
+// copy_hook(i), i = 0..3: called in slots 1, 5, 9, 13 (PENDING only: among the matrix
+// instructions of the score product, away from the vector work), for the caller's global->LDS
+// copies.
 template <typename T, int D, bool PENDING, typename Hook>
 __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb_ahead,
                                           const uint16_t* vb_prev, WideRegs<D>& g,
@@ -359,7 +360,7 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
     // vector work of slot s
     auto valu = [&](int s) __attribute__((always_inline)) {
         if (PENDING) {
-            if ((s & 7) == 3) copy_hook(s >> 3);
+            if (s < 16 && (s & 3) == 1) copy_hook(s >> 2);
             // 32 keys through slots 14..29, two per slot, then the last coefficients and the
             // row sums.  (Measured: a wavefront's vector instructions do not run beside its own
             // matrix instructions whatever their order, and every change from one kind to the
