@@ -21,6 +21,7 @@ def fresh(w, seed):
     ("prefill split", 1, 2, 2, 130, 900, 64, "f16", False, flashd.VARIANT_TILE, 3),
     ("decode", 4, 16, 4, 1, 3000, 128, "bf16", False, flashd.VARIANT_AUTO, 4),
     ("per key", 1, 2, 1, 40, 200, 64, "f32", True, flashd.VARIANT_PER_KEY, 2),
+    ("prefill, 256 rows", 1, 4, 2, 512, 1100, 128, "bf16", True, flashd.VARIANT_TILE_256, 1),
 ])
 def test_graph_replays_equal_eager(case):
     name, B, Hq, Hkv, Lq, Lk, d, dtype, causal, variant, splits = case
