@@ -361,13 +361,15 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
     auto valu = [&](int s) __attribute__((always_inline)) {
         if (PENDING) {
             if (s < 16 && (s & 3) == 1) copy_hook(s >> 2);
-            // 32 keys through slots 14..29, two per slot, then the last coefficients and the
-            // row sums.  (Measured: a wavefront's vector instructions do not run beside its own
-            // matrix instructions whatever their order, and every change from one kind to the
-            // other costs a little; one key per slot over the whole step ran 3.4 % slower than
-            // this, all vector work in one piece between the two products the same as this.)
-            if (s >= 14 && s < 30) { tick(2 * (s - 14)); tick(2 * (s - 14) + 1); }
-            else if (s == 30) { A(31); B(30); B(31); }
+            // 32 keys through slots 15..30, two per slot, then the last coefficients.
+            // (Measured: a wavefront's vector instructions do not run beside its own matrix
+            // instructions whatever their order, and every change from one kind to the other
+            // costs a little; one key per slot over the whole step ran 3.4 % slower than two
+            // per slot from slot 14 on, all vector work in one piece between the two products
+            // the same; starting at an odd slot, 11, 13 or 15, is another 3 % ahead of starting
+            // at 12, 14 or 16.)
+            if (s >= 15 && s < 31) { tick(2 * (s - 15)); tick(2 * (s - 15) + 1); }
+            else if (s == 31) { A(31); B(30); B(31); }
         } else {
             tick(2 * s);
             tick(2 * s + 1);
