@@ -84,8 +84,8 @@ typedef enum {
                                           interleaved by hand) where it can serve the call:
                                           f16/bf16, d = 128, Lq a multiple of 256, no splits,
                                           no state; any other call runs as TILE.  Same
-                                          arithmetic; measured a few percent ahead of TILE
-                                          on long inputs and behind it on short causal
+                                          arithmetic; measured 7 to 18 % ahead of TILE on
+                                          long inputs and behind it on short causal
                                           ones: the automatic choice takes it where it is
                                           ahead (flashd_auto_variant)                      */
 } flashd_variant;

@@ -38,8 +38,8 @@ int validate_shape(const Shape& s) {
 // kernel over batch sizes, head counts and lengths): it needs a workgroup per compute unit to
 // be busy at all (256 of them; twice that under a causal mask, whose row tiles differ in
 // length), and row tiles long enough that the blocks its fused steps take outweigh the first,
-// the last and the masked ones: 2048 keys without a mask (+ 2 to 4 % there, + 7 to 13 % from
-// 4096 keys on), 8192 under a causal mask (+ 3 to 6 % there, + 9 to 13 % at 16384; - 2 % at 4096).
+// the last and the masked ones: 2048 keys without a mask (+ 7 % there, + 12 to 18 % from 4096
+// keys on), 8192 under a causal mask (+ 7 to 12 % there, + 13 to 18 % at 16384; level at 4096).
 // The kernel itself says which calls it can serve at all (wide_applies()).
 bool prefers_256_rows(const Shape& s, bool causal) {
     if (s.d != 128 || s.dtype == FLASHD_F32 || s.Lq % 256 != 0) return false;
