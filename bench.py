@@ -176,7 +176,7 @@ def variant_legs(w, sets, steps, warmup):
             ("tile_blend", flashd.VARIANT_TILE_BLEND)]
     if auto_variant(w) == flashd.VARIANT_TILE_256:
         legs.append(("tile_128_rows", flashd.VARIANT_TILE))
-    elif w.d == 128 and w.Lq % 256 == 0:
+    elif w.d == 128:
         legs.append(("tile_256_rows", flashd.VARIANT_TILE_256))
     for key, var in legs:
         def step_var(i, var=var):

@@ -82,8 +82,8 @@ typedef enum {
     FLASHD_VARIANT_TILE_256 = 5        /* TILE on the kernel with 256 query rows per workgroup
                                           (one wavefront per SIMD, matrix and vector work
                                           interleaved by hand) where it can serve the call:
-                                          f16/bf16, d = 128, Lq a multiple of 256, no splits,
-                                          no state; any other call runs as TILE.  Same
+                                          f16/bf16, d = 128, no splits, no state (rows past
+                                          the end of a head's last 256 are not stored); any other call runs as TILE.  Same
                                           arithmetic; measured 7 to 18 % ahead of TILE on
                                           long inputs and behind it on short causal
                                           ones: the automatic choice takes it where it is
@@ -135,7 +135,7 @@ int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
 /*
  * The variant flashd_attn_fwd (FLASHD_VARIANT_AUTO) runs for this problem: PER_KEY for f32,
  * else TILE, or TILE_256 for calls that kernel can serve and was measured faster on (d = 128,
- * Lq a multiple of 256, one split, at least a workgroup per compute unit, from 2048 keys on
+ * one split, at least a workgroup per compute unit, from 2048 keys on
  * without a mask and 8192 with one).  Host-only; -1 for invalid arguments.  (Decode shapes,
  * (Hq / Hkv) * Lq <= 32, report TILE: they run the tile form on the split-K decode kernel.)
  */

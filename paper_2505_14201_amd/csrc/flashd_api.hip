@@ -42,8 +42,8 @@ int validate_shape(const Shape& s) {
 // keys on), 8192 under a causal mask (+ 7 to 12 % there, + 13 to 18 % at 16384; level at 4096).
 // The kernel itself says which calls it can serve at all (wide_applies()).
 bool prefers_256_rows(const Shape& s, bool causal) {
-    if (s.d != 128 || s.dtype == FLASHD_F32 || s.Lq % 256 != 0) return false;
-    const long wgs = (long)s.B * s.Hq * (s.Lq / 256);
+    if (s.d != 128 || s.dtype == FLASHD_F32) return false;
+    const long wgs = (long)s.B * s.Hq * ((s.Lq + 255) / 256);
     return causal ? (wgs >= 512 && s.Lk >= 8192) : (wgs >= 256 && s.Lk >= 2048);
 }
 

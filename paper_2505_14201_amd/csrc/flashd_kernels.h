@@ -24,7 +24,7 @@ constexpr int kTileModeLazySkipV = 3;
 // Alg. 3 on key tiles (matrix cores, f16/bf16).  With p.splits > 1 also folds the partials.
 hipError_t launch_tile(const Problem& p, int mode, hipStream_t st);
 
-// The 256-row kernel (variant TILE_256: f16/bf16, d = 128, TILE, Lq a multiple of 256, unsplit,
+// The 256-row kernel (variant TILE_256: f16/bf16, d = 128, TILE, unsplit,
 // no state in or out); launch_tile hands over to it where the call asks for it and
 // wide_applies() says it can serve it.
 bool wide_applies(const Problem& p, int mode);

@@ -30,8 +30,8 @@
 // blocks of a causal mask, the tail), and any block under a negative scale, take the plain
 // steps (wide_first_general / wide_second).
 //
-// Serves f16/bf16, d = 128, Lq a multiple of 256, unsplit calls without state in or out
-// (wide_applies()); everything else stays with the 128-row kernel.
+// Serves f16/bf16, d = 128, unsplit calls without state in or out (wide_applies()); everything
+// else stays with the 128-row kernel.
 #include "flashd_common.h"
 #include "flashd_kernels.h"
 #include "flashd_mma.h"
@@ -587,12 +587,13 @@ void wide_kernel(Problem p, TileSched sc) {
         const int lane_q = wide_lane_id();
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) {
-            const int row = cur.wrow0 + 32 * rb + (lane_q & 31);
+            // rows past the end stand in for the last row (the same arithmetic on the same
+            // numbers; nothing of them is stored)
+            const int row = min(cur.wrow0 + 32 * rb + (lane_q & 31), p.Lq - 1);
             nvis[rb] = visible_count(p, row);
-            const int qr = min(row, p.Lq - 1);
 #pragma unroll
             for (int kk = 0; kk < NKK; ++kk)
-                qload[rb][kk] = *reinterpret_cast<const u32x4*>(cur.qg + (size_t)qr * D + 16 * kk +
+                qload[rb][kk] = *reinterpret_cast<const u32x4*>(cur.qg + (size_t)row * D + 16 * kk +
                                                                 8 * (lane_q >> 5));
             g.st[rb] = {0.0f, 0.0f, 0.0f};
         }
@@ -614,8 +615,13 @@ void wide_kernel(Problem p, TileSched sc) {
         // The last block a fused step can take: every key visible to every row of the
         // wavefront, and a block after it whose scores it forms.  (Block 0 never: rows are
         // still empty.)
-        const int b_fused = c_log2 >= 0.0f
-                                ? min((cur.wmin - cur.jbase) / kWideKB - 1, nbw - 2) : -1;
+        int wmin = cur.wmin;        // keys every row of the wavefront sees
+        if (cur.wrow0 < p.Lq && cur.wrow0 + 32 * kWideRB > p.Lq) {
+            // the wavefront's rows run past the end: those that exist decide
+            int most;
+            visible_range(p, cur.wrow0, p.Lq - 1, most, wmin);
+        }
+        const int b_fused = c_log2 >= 0.0f ? min((wmin - cur.jbase) / kWideKB - 1, nbw - 2) : -1;
         bool pending = false;       // the output product of the block before is still to come
         bool k_ahead = false;       // K operands 0..2 of the next score product are on their way
         // Tile t sits in K slot t % 4 and V slot t % 4.  Period t: start the copies of K(t + 3)
@@ -824,8 +830,7 @@ bool wide_applies(const Problem& p, int mode) {
     if (mode != kModeLazy) return false;
     if (p.splits != 1 || p.partial || p.merge || p.from_state || !p.store_o) return false;
     if (p.state_out != nullptr || p.kv8) return false;
-    if ((int)p.Li.d != p.Lq) return false;
-    return p.Lq % kWideBM == 0;
+    return (int)p.Li.d == p.Lq;
 }
 
 template <typename T, int D>

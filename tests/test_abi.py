@@ -16,6 +16,11 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_HEADDIM, E_GQA, E_ALIGN, E_WS, E_HIP, E_ARCH, E_
 
 P = 0x1000          # a non-null, 16-byte aligned fake pointer; never dereferenced on these paths
 
+# A call whose arguments are all valid goes on to launch a kernel where there is a GPU, and the
+# fake pointers would then be dereferenced on the device: such calls are only made without one
+# (they end in FLASHD_E_HIP there).
+NO_GPU = not torch.cuda.is_available()
+
 
 def fwd(q=P, k=P, v=P, o=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=8, d=64, causal=0, scale=0.125,
         dtype=flashd.BF16):
@@ -151,7 +156,7 @@ def test_automatic_choice_of_the_prefill_kernel():
     assert V(1, 16, 16, 2048, 2048, 128, BF, False) == T       # 128 workgroups
     assert V(1, 32, 32, 1024, 1024, 128, BF, False) == T       # short rows of keys
     assert V(2, 16, 16, 4096, 4096, 64, F16, False) == T       # d = 64
-    assert V(1, 32, 32, 4000, 4096, 128, BF, False) == T       # Lq not a multiple of 256
+    assert V(1, 32, 32, 4000, 4096, 128, BF, False) == W       # Lq need not be a multiple of 256
     assert V(1, 4, 4, 128, 128, 64, flashd.F32, False) == flashd.VARIANT_PER_KEY
     assert V(64, 32, 8, 1, 8192, 128, BF, False) == T          # decode shape
     assert V(1, 32, 32, 0, 4096, 128, BF, False) == -1
@@ -183,7 +188,8 @@ def test_skip_stats_argument_errors():
     assert stats(Hq=5) == E_GQA
     assert stats(q=P + 8) == E_ALIGN
     assert stats(counts=P + 4) == E_ALIGN
-    assert stats(counts=P + 8) != E_ALIGN          # 8-byte alignment is enough for the counters
+    if NO_GPU:
+        assert stats(counts=P + 8) == E_HIP        # 8-byte alignment is enough for the counters
 
 
 def fwd_state(q=P, k=P, v=P, o=P, sin=None, sout=P, B=1, Hq=4, Hkv=2, Lq=8, Lk=512, d=64,
@@ -196,7 +202,8 @@ def test_state_entry_point_argument_errors():
     for name in ("q", "k", "v"):
         assert fwd_state(**{name: None}) == E_NULL
     assert fwd_state(o=None, sout=None) == E_NULL            # nothing to write
-    assert fwd_state(o=None) != E_NULL and fwd_state(sout=None) != E_NULL
+    if NO_GPU:
+        assert fwd_state(o=None) == E_HIP and fwd_state(sout=None) == E_HIP
     assert fwd_state(Lq=0) == E_SHAPE
     assert fwd_state(d=96) == E_HEADDIM
     assert fwd_state(Hq=3) == E_GQA
@@ -217,7 +224,8 @@ def test_fp8_entry_point_argument_errors():
     assert fwd_kv8(Hq=7) == E_GQA
     assert fwd_kv8(k=P + 8) == E_ALIGN
     assert fwd_kv8(dtype=flashd.F32) == E_VARIANT            # q and o must be f16 or bf16
-    assert fwd_kv8(Hq=8, Hkv=2, Lq=9) not in (E_VARIANT, E_NULL, E_SHAPE, E_ALIGN)
+    if NO_GPU:
+        assert fwd_kv8(Hq=8, Hkv=2, Lq=9) == E_HIP
 
 
 def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):

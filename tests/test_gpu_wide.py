@@ -35,6 +35,9 @@ SHAPES = [
     (2, 2, 1, 768, 700),       # ragged key tail; causal rows that see few keys
     (1, 3, 3, 1024, 1000),
     (1, 1, 1, 256, 4160),      # long rows of keys: 65 tiles, the copy ring wraps many times
+    (1, 2, 2, 300, 500),       # rows past the end of the last row tile: one wavefront's block, then whole wavefronts
+    (2, 3, 1, 513, 1100),      # one row in the last row tile
+    (1, 2, 2, 40, 2048),       # less than one wavefront of rows
 ]
 
 
@@ -90,7 +93,6 @@ def test_wide_kernel_negative_and_zero_scale(scale):
 
 
 @pytest.mark.parametrize("shape,dtype,d,splits", [
-    ((1, 2, 2, 300, 500), "bf16", 128, 1),     # Lq not a multiple of 256
     ((1, 2, 2, 256, 512), "bf16", 64, 1),      # d = 64
     ((1, 2, 2, 256, 4096), "f16", 128, 2),     # split keys
 ])
