@@ -316,12 +316,18 @@ __device__ __forceinline__ void wide_request_first_k(const uint16_t* kb, const W
 // copy_hook(i), i = 0..3: called in slots 1, 5, 9, 13 (PENDING only: among the matrix
 // instructions of the score product, away from the vector work), for the caller's global->LDS
 // copies.
-template <typename T, int D, bool PENDING, typename Hook>
+// MASKED: block b may be one a mask applies to.  lim[rb]: the lane's keys of the block are
+// those at offsets 8 (r >> 2) + (r & 3), r = 0..15, from the key in its score register 0, and
+// the ones at offsets >= lim[rb] are hidden from its row of row block rb: their score counts as
+// -inf and their coefficient is 0.  (Two more vector instructions per key; no row may be empty
+// as for any fused step.)
+template <typename T, int D, bool PENDING, bool MASKED, typename Hook>
 __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb_ahead,
                                           const uint16_t* vb_prev, WideRegs<D>& g,
                                           const f32x16 (&acc)[kWideRB], f32x16 (&accn)[kWideRB],
                                           float c_log2, uint32_t ones, const WidePacked& prev,
-                                          WidePacked& cur, const Hook& copy_hook) {
+                                          WidePacked& cur, const int (&lim)[kWideRB],
+                                          const Hook& copy_hook) {
     static_assert(D == 128 && kWideRB == 2, "the slots below are laid out for this shape");
     constexpr int NDB = D / 32;
     float ref[kWideRB], l[kWideRB];
@@ -333,7 +339,13 @@ __device__ __forceinline__ bool wide_step(const uint16_t* kb, const uint16_t* kb
     // key k of the 32: row block k & 1, score register k >> 1
     float x[33], pe[32];
     auto F = [&](int k) __attribute__((always_inline)) {
-        if (k < 32) x[k] = fmaf(acc[k & 1][k >> 1], c_log2, -ref[k & 1]);
+        if (k < 32) {
+            x[k] = fmaf(acc[k & 1][k >> 1], c_log2, -ref[k & 1]);
+            if (MASKED) {
+                const int r = k >> 1;
+                x[k] = (8 * (r >> 2) + (r & 3) >= lim[k & 1]) ? -__builtin_inff() : x[k];
+            }
+        }
     };
     auto X = [&](int k) __attribute__((always_inline)) {
         if (k < 32) pe[k] = exp2_fast(x[k]);
@@ -457,7 +469,8 @@ __device__ __forceinline__ void wide_first_general(WideRegs<D>& g, const f32x16 
         c.ref[rb] = move ? mref : g.st[rb].R;
         c.f[rb] = empty ? 0.0f : (move ? exp2_fast(g.st[rb].R - mref) : 1.0f);
         c.empty[rb] = empty;
-        if (__builtin_amdgcn_ballot_w64(c.f[rb] != 1.0f) != 0) wide_scale_u<D>(rb, c.f[rb]);
+        // (an empty row holds zeros: nothing to scale)
+        if (__builtin_amdgcn_ballot_w64(c.f[rb] != 1.0f && !empty) != 0) wide_scale_u<D>(rb, c.f[rb]);
         int nv = nvis[rb];
         asm volatile("" : "+v"(nv));      // keep these compares apart from row_top_score's
         f32x4 ps = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -612,16 +625,22 @@ void wide_kernel(Problem p, TileSched sc) {
         WidePacked pk[2];                // coefficients of block b (a fused step's) in pk[b % 2]
         if (nbw > 0) wide_scores<T, D>(lds, g, acc[0]);
 
-        // The last block a fused step can take: every key visible to every row of the
-        // wavefront, and a block after it whose scores it forms.  (Block 0 never: rows are
-        // still empty.)
+        // The last block a fused step can take: the wavefront's last (the scores the step forms
+        // beside it are then those of a block the wavefront has no part in, or of whatever the
+        // next K slot holds, and nobody reads them; that costs less than a second kind of step
+        // would cost the others in registers and code).  Blocks a mask applies to included, as
+        // long as no row is still empty:
+        // never block 0, and no block at all if some row of the wavefront sees no key in block
+        // 0, or under a negative scale.
+        const int nolim[kWideRB] = {64, 64};
         int wmin = cur.wmin;        // keys every row of the wavefront sees
         if (cur.wrow0 < p.Lq && cur.wrow0 + 32 * kWideRB > p.Lq) {
             // the wavefront's rows run past the end: those that exist decide
             int most;
             visible_range(p, cur.wrow0, p.Lq - 1, most, wmin);
         }
-        const int b_fused = c_log2 >= 0.0f ? min((wmin - cur.jbase) / kWideKB - 1, nbw - 2) : -1;
+        const int b_nomask = (wmin - cur.jbase) / kWideKB - 1;    // the last block without a mask
+        const int b_fused = (c_log2 >= 0.0f && wmin > cur.jbase) ? nbw - 1 : -1;
         bool pending = false;       // the output product of the block before is still to come
         bool k_ahead = false;       // K operands 0..2 of the next score product are on their way
         // Tile t sits in K slot t % 4 and V slot t % 4.  Period t: start the copies of K(t + 3)
@@ -652,7 +671,8 @@ void wide_kernel(Problem p, TileSched sc) {
         auto nohook = [](int) __attribute__((always_inline)) {};
         // The last period both of whose blocks fused steps can take while its copies (both
         // there, both of tiles that lie wholly inside the keys) go out one at a time.
-        const int t_hi = min(min((b_fused - 1) >> 1, n - 4), (p.Lk - cur.jbase) / kBC - 4);
+        const int t_hi = min(min(min((b_fused - 1) >> 1, (b_nomask - 1) >> 1), n - 4),
+                             (p.Lk - cur.jbase) / kBC - 4);
         // 0: nothing of period t is done; 1: a fused step found block 2 t risky (the scores of
         // the next block are there, the K copies are out); 2: the same for block 2 t + 1 (both
         // copies are out)
@@ -662,16 +682,16 @@ void wide_kernel(Problem p, TileSched sc) {
             // taken by fused steps that find nothing risky
             if (pending) {
                 while (t <= t_hi) {
-                    if (__builtin_expect(wide_step<T, D, true>(kslot(0) + kWideKB * D, kslot(1),
-                                                               vslot(3) + kWideKB * D, g, acc[0],
-                                                               acc[1], c_log2, ones, pk[1], pk[0],
-                                                               khook), 0)) {
+                    if (__builtin_expect(wide_step<T, D, true, false>(
+                                             kslot(0) + kWideKB * D, kslot(1),
+                                             vslot(3) + kWideKB * D, g, acc[0], acc[1], c_log2,
+                                             ones, pk[1], pk[0], nolim, khook), 0)) {
                         resume = 1;
                         break;
                     }
-                    if (__builtin_expect(wide_step<T, D, true>(kslot(1), kslot(1) + kWideKB * D,
-                                                               vslot(0), g, acc[1], acc[0], c_log2,
-                                                               ones, pk[0], pk[1], vhook), 0)) {
+                    if (__builtin_expect(wide_step<T, D, true, false>(
+                                             kslot(1), kslot(1) + kWideKB * D, vslot(0), g, acc[1],
+                                             acc[0], c_log2, ones, pk[0], pk[1], nolim, vhook), 0)) {
                         resume = 2;
                         break;
                     }
@@ -710,20 +730,34 @@ void wide_kernel(Problem p, TileSched sc) {
             auto block = [&](auto kbc) __attribute__((always_inline)) {
                 constexpr int KB = decltype(kbc)::value;
                 const int b = 2 * t + KB;
-                if (b >= nbw) return;
                 const uint16_t* kn = KB == 0 ? kcur + kWideKB * D : knext;
                 const uint16_t* ka = KB == 0 ? knext : knext + kWideKB * D;
                 const uint16_t* vp = KB == 0 ? vprev + kWideKB * D : vcur;
+                if (b >= nbw) {
+                    // past the wavefront's last block: that one's output product, if a fused
+                    // step has left it
+                    if (pending) wide_pv<T, D>(vp, g, pk[KB ^ 1].g0, pk[KB ^ 1].g1);
+                    pending = false;
+                    return;
+                }
                 bool have_next = false;
                 if (b >= 1 && b <= b_fused) {
                     bool risky;
+                    // offsets from the key in the lane's score register 0 at which its rows'
+                    // hidden keys begin (none: 64)
+                    int lim[kWideRB];
+#pragma unroll
+                    for (int rb = 0; rb < kWideRB; ++rb)
+                        lim[rb] = b > b_nomask ? nvis[rb] - (cur.jbase + b * kWideKB + 4 * hh) : 64;
                     if (pending) {
-                        risky = wide_step<T, D, true>(kn, ka, vp, g, acc[KB], acc[KB ^ 1], c_log2,
-                                                      ones, pk[KB ^ 1], pk[KB], nohook);
+                        risky = wide_step<T, D, true, true>(kn, ka, vp, g, acc[KB], acc[KB ^ 1],
+                                                            c_log2, ones, pk[KB ^ 1], pk[KB], lim,
+                                                            nohook);
                     } else {
                         if (!k_ahead) wide_request_first_k<D>(kn, g);
-                        risky = wide_step<T, D, false>(kn, ka, vp, g, acc[KB], acc[KB ^ 1], c_log2,
-                                                       ones, pk[KB ^ 1], pk[KB], nohook);
+                        risky = wide_step<T, D, false, true>(kn, ka, vp, g, acc[KB], acc[KB ^ 1],
+                                                             c_log2, ones, pk[KB ^ 1], pk[KB], lim,
+                                                             nohook);
                     }
                     k_ahead = true;
                     have_next = true;
@@ -765,7 +799,8 @@ void wide_kernel(Problem p, TileSched sc) {
             asm volatile("" ::: "memory");
             ++t;
         }
-        // (the wavefront's last block is never a fused step's, so nothing is pending here)
+        // the output product of the row tile's last block, if a fused step has left it
+        if (pending) wide_pv<T, D>(vs0 + ((n - 1) & 3) * kTile + kWideKB * D, g, pk[1].g0, pk[1].g1);
 
         // ---- epilogue: o = beta U (FLASH-D) or U / l (Alg. 2), staged through LDS so that the
         // global stores are 16 bytes per lane and whole rows are contiguous.  Every wavefront
