@@ -115,9 +115,9 @@ __device__ __forceinline__ void wide_copy(const uint16_t* src, int j0, int Lk, c
 // constant once the loops around them are unrolled.  The compiler does not see these as
 // matrix instructions, so a result is only read by vector instructions that are known to come
 // at least 20 wait states later (mma_fence() where nothing else lies between).
-__device__ __forceinline__ void wide_set_q_n(int n, u32x4 q) {
+__device__ __forceinline__ void wide_read_q_n(int n, uint32_t addr) {
     switch (n) {
-#define FLASHD_CASE(N) case N: wide_set_q<N>(q); break;
+#define FLASHD_CASE(N) case N: wide_read_q<N>(addr); break;
         FLASHD_CASE(0) FLASHD_CASE(1) FLASHD_CASE(2) FLASHD_CASE(3) FLASHD_CASE(4) FLASHD_CASE(5)
         FLASHD_CASE(6) FLASHD_CASE(7) FLASHD_CASE(8) FLASHD_CASE(9) FLASHD_CASE(10) FLASHD_CASE(11)
         FLASHD_CASE(12) FLASHD_CASE(13) FLASHD_CASE(14) FLASHD_CASE(15)
@@ -548,8 +548,17 @@ void wide_kernel(Problem p, TileSched sc) {
     constexpr int NKK = D / 16;
     constexpr int NDB = D / 32;
     constexpr int kTile = kBC * D;
-    __shared__ __align__(1024) uint16_t lds[8 * kTile];       // K0 K1 K2 K3 V0 V1 V2 V3
+    __shared__ __align__(1024) uint16_t lds[9 * kTile];       // K0 K1 K2 K3 V0 V1 V2 V3 X
     uint16_t* const vs0 = lds + 4 * kTile;
+    // Where the Q rows of a row tile land, 64 rows (a wavefront's) per slot: the four slots that
+    // the first copies of K and V do not fill (K3, V2, V3 and X, which has no other use).  Laid
+    // out as a K tile, whose operand read is the read of a Q fragment (row = lane % 32, 16 bytes
+    // at element 16 kk + 8 hh), and copied like one: whole rows per instruction.  (Fetched
+    // straight into registers, 16 bytes per lane from 32 different rows per instruction, the
+    // same bytes kept the address unit busy three times as long.)
+    auto qslot = [&](int w) __attribute__((always_inline)) {
+        return lds + (w == 0 ? 3 : w == 3 ? 8 : 5 + w) * kTile;
+    };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -582,6 +591,12 @@ void wide_kernel(Problem p, TileSched sc) {
         // the staging reads of the row tile before must be over before its LDS is refilled
         if (!first) __syncthreads();
         const int n = cur.n;
+        {
+            const int m0 = cur.wrow0 - 32 * kWideRB * wave;     // the row tile's first row
+#pragma unroll
+            for (int w = 0; w < kNW; ++w)
+                wide_copy<D, false>(cur.qg, m0 + 32 * kWideRB * w, p.Lq, dl, wave, lane, qslot(w));
+        }
         if (n > 0) {
             wide_copy<D, false>(cur.kg, cur.jbase, p.Lk, dl, wave, lane, lds);
             wide_copy<D, true>(cur.vg, cur.jbase, p.Lk, dl, wave, lane, vs0);
@@ -593,7 +608,6 @@ void wide_kernel(Problem p, TileSched sc) {
         if (n > 2)
             wide_copy<D, false>(cur.kg, cur.jbase + 2 * kBC, p.Lk, dl, wave, lane, lds + 2 * kTile);
         int nvis[kWideRB];
-        u32x4 qload[kWideRB][NKK];
         wide_zero_u();
         // (the lane index afresh, here and in the epilogue: what is formed from it then does
         // not sit in registers across the tile loop)
@@ -604,10 +618,6 @@ void wide_kernel(Problem p, TileSched sc) {
             // numbers; nothing of them is stored)
             const int row = min(cur.wrow0 + 32 * rb + (lane_q & 31), p.Lq - 1);
             nvis[rb] = visible_count(p, row);
-#pragma unroll
-            for (int kk = 0; kk < NKK; ++kk)
-                qload[rb][kk] = *reinterpret_cast<const u32x4*>(cur.qg + (size_t)row * D + 16 * kk +
-                                                                8 * (lane_q >> 5));
             g.st[rb] = {0.0f, 0.0f, 0.0f};
         }
         // 32-key blocks this wavefront takes part in: those that start before its rows' last
@@ -615,11 +625,21 @@ void wide_kernel(Problem p, TileSched sc) {
         const int nbw = min(2 * n, max(0, (cur.wmax - cur.jbase + kWideKB - 1) / kWideKB));
         wait_copies();
         __syncthreads();
-        // the Q fragments go to their accumulation registers
+        // the Q fragments go to their accumulation registers; once every wavefront has read
+        // its own, the slots they came from are free for the copies of the first period
+        // (the slot's address is made opaque here, so that the sixteen addresses below are
+        // formed here and not kept in registers from the start of the kernel on)
+        uint32_t qbase = lds_byte_address(qslot(wave));
+        asm volatile("" : "+v"(qbase));
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb)
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) wide_set_q_n(8 * rb + kk, qload[rb][kk]);
+            for (int kk = 0; kk < NKK; ++kk)
+                wide_read_q_n(8 * rb + kk, qbase + 2u * (uint32_t)(g.kaddr[kk] + 32 * rb * D));
+        wide_wait_lds<0>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
 
         f32x16 acc[2][kWideRB];          // scores of block b live in acc[b % 2]
         WidePacked pk[2];                // coefficients of block b (a fused step's) in pk[b % 2]
