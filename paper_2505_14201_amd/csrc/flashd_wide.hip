@@ -43,6 +43,10 @@ namespace flashd {
 constexpr int kWideRB = 2;                      // 32-row blocks per wavefront
 constexpr int kWideBM = 32 * kWideRB * kNW;     // query rows per workgroup
 constexpr int kWideKB = 32;                     // keys per step of a wavefront (half a tile)
+// The least a row's coefficients of block 0 must add up to when zero stood in for the row's
+// reference (the largest of them is then at least 2^-8: far inside the range of either storage
+// type, whose rounding of a coefficient is relative).
+constexpr float kWideMinStart = 0.125f;
 
 // A row's state in this kernel, the lazy form of flashd_mma.h with the blend factor kept as its
 // reciprocal: o = U / l, where l = 1 / beta is the sum of 2^{s_j - R} over the keys seen so far.
@@ -649,9 +653,10 @@ void wide_kernel(Problem p, TileSched sc) {
         // beside it are then those of a block the wavefront has no part in, or of whatever the
         // next K slot holds, and nobody reads them; that costs less than a second kind of step
         // would cost the others in registers and code).  Blocks a mask applies to included, as
-        // long as no row is still empty:
-        // never block 0, and no block at all if some row of the wavefront sees no key in block
-        // 0, or under a negative scale.
+        // long as no row is still empty: not if some row of the wavefront sees no key in block 0
+        // (nor under a negative scale).  Block 0 as well, with zero standing in for the rows'
+        // reference: good if every row's coefficients then add up to something between
+        // kWideMinStart and the limit of any fused step, else the plain steps take the block.
         const int nolim[kWideRB] = {64, 64};
         int wmin = cur.wmin;        // keys every row of the wavefront sees
         if (cur.wrow0 < p.Lq && cur.wrow0 + 32 * kWideRB > p.Lq) {
@@ -761,7 +766,7 @@ void wide_kernel(Problem p, TileSched sc) {
                     return;
                 }
                 bool have_next = false;
-                if (b >= 1 && b <= b_fused) {
+                if (b <= b_fused) {
                     bool risky;
                     // offsets from the key in the lane's score register 0 at which its rows'
                     // hidden keys begin (none: 64)
@@ -778,6 +783,19 @@ void wide_kernel(Problem p, TileSched sc) {
                         risky = wide_step<T, D, false, true>(kn, ka, vp, g, acc[KB], acc[KB ^ 1],
                                                              c_log2, ones, pk[KB ^ 1], pk[KB], lim,
                                                              nohook);
+                    }
+                    if (b == 0 && !risky) {
+                        // the rows were empty and zero was their reference
+                        bool low = false;
+#pragma unroll
+                        for (int rb = 0; rb < kWideRB; ++rb)
+                            low = low || !(pair_sum(g.st[rb].l) >= kWideMinStart);
+                        risky = __builtin_amdgcn_ballot_w64(low) != 0;
+#pragma unroll
+                        for (int rb = 0; rb < kWideRB; ++rb) {
+                            g.st[rb].l = risky ? 0.0f : g.st[rb].l;
+                            g.st[rb].one = risky ? 0.0f : 1.0f;
+                        }
                     }
                     k_ahead = true;
                     have_next = true;

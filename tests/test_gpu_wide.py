@@ -84,6 +84,29 @@ def test_wide_kernel_staircase_of_scores(dtype):
     check(got, ref, DT[dtype], f"staircase {dtype}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("level", [-40.0, -4.0, 30.0])
+def test_wide_kernel_first_block_far_from_zero(dtype, causal, level):
+    """The first block of a row tile takes a fused step with zero standing in for the rows'
+    reference; scores that all lie far below zero (the coefficients would vanish), a little
+    below (the sum falls short of the least that is trusted) or far above (they would overflow)
+    must send it through the plain steps instead, and rows that see only a key or two must
+    come out right either way."""
+    torch.manual_seed(17)
+    Lq, Lk, d = 512, 768, 128
+    q = torch.zeros(1, 2, Lq, d)
+    q[..., 0] = 1.0
+    q[..., 1:] = 0.1 * torch.randn(2, Lq, d - 1)
+    k = 0.1 * torch.randn(1, 2, Lk, d)
+    k[..., 0] = level + 0.5 * torch.randn(2, Lk)
+    v = torch.randn(1, 2, Lk, d)
+    q, k, v = (t.to(DT[dtype]) for t in (q, k, v))
+    got = run_flashd(q, k, v, causal, 1.0, WIDE, 1)
+    ref = oa.attn(q, k, v, causal, 1.0)
+    check(got, ref, DT[dtype], f"first block at {level} {dtype} causal={causal}")
+
+
 @pytest.mark.parametrize("scale", [-0.09, 0.0])
 def test_wide_kernel_negative_and_zero_scale(scale):
     w = synthetic.small("wide scale", 1, 2, 2, 256, 600, 128, "bf16", True, seed=9500)
