@@ -37,14 +37,17 @@ int validate_shape(const Shape& s) {
 // Where the automatic choice takes the 256-row prefill kernel (measured against the 128-row
 // kernel over batch sizes, head counts and lengths): it needs a workgroup per compute unit to
 // be busy at all (256 of them; twice that under a causal mask, whose row tiles differ in
-// length), and row tiles long enough that the blocks its fused steps take outweigh the first,
-// the last and the masked ones: 2048 keys without a mask (+ 7 % there, + 12 to 18 % from 4096
-// keys on), 8192 under a causal mask (+ 7 to 12 % there, + 13 to 18 % at 16384; level at 4096).
-// The kernel itself says which calls it can serve at all (wide_applies()).
+// length and run in pairs), and row tiles long enough to outweigh what it pays at every change
+// of row tile with only one workgroup on the compute unit (about 8 us, four to five periods of
+// 64 keys): 1536 keys without a mask (+ 8 % at 1536 and 2048, + 12 to 16 % from 4096 on; level
+// at 1024), and under a causal mask rows that see 1536 keys on average, Lk - Lq / 2 (+ 6 % at
+// 3072 x 3072, + 8 to 10 % at 4096, + 14 to 16 % from 8192 on and at 1000 x 3000; level at
+// 2048 x 2048, 0.90 at 1024, and 3 to 6 % behind where the pairs do not fill a whole number of
+// rounds).  The kernel itself says which calls it can serve at all (wide_applies()).
 bool prefers_256_rows(const Shape& s, bool causal) {
     if (s.d != 128 || s.dtype == FLASHD_F32) return false;
     const long wgs = (long)s.B * s.Hq * ((s.Lq + 255) / 256);
-    return causal ? (wgs >= 512 && s.Lk >= 8192) : (wgs >= 256 && s.Lk >= 2048);
+    return causal ? (wgs >= 512 && (long)s.Lk - s.Lq / 2 >= 1536) : (wgs >= 256 && s.Lk >= 1536);
 }
 
 int resolve_variant(const Shape& s, int variant) {

@@ -149,12 +149,16 @@ def test_automatic_choice_of_the_prefill_kernel():
     assert V(1, 32, 32, 16384, 16384, 128, BF, False) == W     # long, no mask
     assert V(4, 32, 32, 2048, 2048, 128, BF, False) == W       # 2048 keys are enough without a mask
     assert V(4, 32, 32, 2048, 2048, 128, BF, True) == T        # the headline shape: short causal rows
-    assert V(1, 32, 32, 4096, 4096, 128, BF, True) == T
+    assert V(1, 32, 32, 4096, 4096, 128, BF, True) == W        # rows see 2048 keys on average
+    assert V(2, 32, 32, 3072, 3072, 128, BF, True) == W        # 1536 on average
+    assert V(8, 32, 8, 512, 2048, 128, BF, True) == W          # short queries late in a long context
+    assert V(8, 32, 32, 1024, 1024, 128, BF, True) == T
     assert V(1, 32, 32, 8192, 8192, 128, F16, True) == W       # 8192 keys under a causal mask
     assert V(1, 8, 8, 8192, 8192, 128, BF, True) == T          # 256 workgroups: too few with a mask
     assert V(1, 8, 8, 8192, 8192, 128, BF, False) == W
     assert V(1, 16, 16, 2048, 2048, 128, BF, False) == T       # 128 workgroups
     assert V(1, 32, 32, 1024, 1024, 128, BF, False) == T       # short rows of keys
+    assert V(4, 32, 32, 1536, 1536, 128, BF, False) == W
     assert V(2, 16, 16, 4096, 4096, 64, F16, False) == T       # d = 64
     assert V(1, 32, 32, 4000, 4096, 128, BF, False) == W       # Lq need not be a multiple of 256
     assert V(1, 4, 4, 128, 128, 64, flashd.F32, False) == flashd.VARIANT_PER_KEY
