@@ -28,7 +28,7 @@ import torch
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16/fp16 matrix peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # profiles/ summary that holds the HBM traffic of each prefill configuration's kernel
-PREFILL_PROFILE = {1: "tile_kernel_bf16_d128_causal_prefill.txt",
+PREFILL_PROFILE = {1: "wide_kernel_bf16_d128_causal_prefill.txt",
                    2: "wide_kernel_bf16_d128_long_noncausal_prefill.txt",
                    4: "tile_kernel_f16_d64_stress_prefill.txt"}
 # fp32 vector peak as published (157.3 TFLOP/s: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz,

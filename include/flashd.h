@@ -136,7 +136,8 @@ int flashd_auto_splits(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype,
  * The variant flashd_attn_fwd (FLASHD_VARIANT_AUTO) runs for this problem: PER_KEY for f32,
  * else TILE, or TILE_256 for calls that kernel can serve and was measured faster on (d = 128,
  * one split, at least a workgroup per compute unit, from 1536 keys on
- * without a mask, and with one where a row sees 1536 keys on average).  Host-only; -1 for invalid arguments.  (Decode shapes,
+ * without a mask, and with one where a row sees 1536 keys on average, or 1024 if the row
+ * tiles come in whole rounds of the compute units).  Host-only; -1 for invalid arguments.  (Decode shapes,
  * (Hq / Hkv) * Lq <= 32, report TILE: they run the tile form on the split-K decode kernel.)
  */
 int flashd_auto_variant(int B, int Hq, int Hkv, int Lq, int Lk, int d, int dtype, int causal);

@@ -41,13 +41,18 @@ int validate_shape(const Shape& s) {
 // of row tile with only one workgroup on the compute unit (about 8 us, four to five periods of
 // 64 keys): 1536 keys without a mask (+ 8 % at 1536 and 2048, + 12 to 16 % from 4096 on; level
 // at 1024), and under a causal mask rows that see 1536 keys on average, Lk - Lq / 2 (+ 6 % at
-// 3072 x 3072, + 8 to 10 % at 4096, + 14 to 16 % from 8192 on and at 1000 x 3000; level at
-// 2048 x 2048, 0.90 at 1024, and 3 to 6 % behind where the pairs do not fill a whole number of
-// rounds).  The kernel itself says which calls it can serve at all (wide_applies()).
+// 3072 x 3072, + 8 to 10 % at 4096, + 14 to 16 % from 8192 on and at 1000 x 3000; 0.90 at
+// 1024).  Rows that see 1024 keys on average (2048 x 2048) are taken where the pairs of row
+// tiles fill a whole number of rounds of the 256 compute units (+ 1 to 3 % then; 3 to 6 %
+// behind otherwise, with compute units idle in the last round).  The kernel itself says
+// which calls it can serve at all (wide_applies()).
 bool prefers_256_rows(const Shape& s, bool causal) {
     if (s.d != 128 || s.dtype == FLASHD_F32) return false;
     const long wgs = (long)s.B * s.Hq * ((s.Lq + 255) / 256);
-    return causal ? (wgs >= 512 && (long)s.Lk - s.Lq / 2 >= 1536) : (wgs >= 256 && s.Lk >= 1536);
+    if (!causal) return wgs >= 256 && s.Lk >= 1536;
+    const long seen = (long)s.Lk - s.Lq / 2;        // keys a row sees on average
+    const bool whole_rounds = s.Lq % 512 == 0 && (wgs / 2) % 256 == 0;
+    return wgs >= 512 && (seen >= 1536 || (seen >= 1024 && whole_rounds));
 }
 
 int resolve_variant(const Shape& s, int variant) {

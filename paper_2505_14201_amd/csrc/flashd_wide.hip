@@ -97,10 +97,13 @@ __device__ __forceinline__ void wide_copy(const uint16_t* src, int j0, int Lk, c
         issue(IntC<0>{}); issue(IntC<1>{});
         if constexpr (NI == 4) { issue(IntC<2>{}); issue(IntC<3>{}); }
     } else {
+        // (the lane index afresh: this path is rare, and the index does not have to be kept for it)
+        (void)lane;
+        const int lane_now = wide_lane_id();
 #pragma unroll 1
         for (int n = 0; n < NI; ++n) {
             const int inst = wave * NI + n;
-            const int slot = inst * 64 + lane;
+            const int slot = inst * 64 + lane_now;
             const int row = slot / C::CPR;
             const int cs = slot % C::CPR;
             const size_t grow = (size_t)min(j0 + row, Lk - 1) * D;
@@ -840,59 +843,66 @@ void wide_kernel(Problem p, TileSched sc) {
         // the output product of the row tile's last block, if a fused step has left it
         if (pending) wide_pv<T, D>(vs0 + ((n - 1) & 3) * kTile + kWideKB * D, g, pk[1].g0, pk[1].g1);
 
-        // ---- epilogue: o = beta U (FLASH-D) or U / l (Alg. 2), staged through LDS so that the
-        // global stores are 16 bytes per lane and whole rows are contiguous.  Every wavefront
-        // is past the last barrier, so all of LDS is free; a wavefront stages its 64 rows in
-        // its own 64 x D elements.  Chunk c of row r sits at chunk position c ^ (r % CPR).
-        uint16_t* stage = lds + wave * (64 * D);
+        // ---- epilogue: o = U / l, staged through LDS so that the global stores are 16 bytes per
+        // lane and cover whole 128-byte lines.  In four passes per wavefront, a row block's 32
+        // rows by 64 columns each, so that the stores of one pass drain while the vector
+        // instructions of the next scale and round (all in one piece, the 64 stores of a
+        // wavefront came after 400 vector instructions and each kind waited for the other).
+        // Every wavefront is past the last barrier and nobody reads K any more: a wavefront
+        // stages in its own 4 KB of K slot 0.  Chunk c of row r sits at chunk position
+        // c ^ ((r / 2) % 8) of the row's 128 bytes.
+        uint16_t* stage = lds + wave * (32 * 64);
         const int lane_e = wide_lane_id();
         const int col_e = lane_e & 31, hh_e = lane_e >> 5;
+        float fin[kWideRB];
 #pragma unroll
         for (int rb = 0; rb < kWideRB; ++rb) {
             // beta = 1 / l, the two lanes' parts added; a row that saw no key stores zeros
             const float lrow = pair_sum(g.st[rb].l);
-            const float fin = lrow > 0.0f ? p.oscale * __builtin_amdgcn_rcpf(lrow) : 0.0f;
-            const int srow = 32 * rb + col_e;
+            fin[rb] = lrow > 0.0f ? p.oscale * __builtin_amdgcn_rcpf(lrow) : 0.0f;
+        }
 #pragma unroll
-            for (int i = 0; i < NDB; ++i) {
-                const f32x16 u = wide_get_u_n(4 * rb + i);
+        for (int pass = 0; pass < 2 * kWideRB; ++pass) {
+            const int rb = pass >> 1, hf = pass & 1;
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const f32x16 u = wide_get_u_n(4 * rb + 2 * hf + ii);
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
-                    const int dc = 32 * i + 8 * gq + 4 * hh_e;
+                    const int dc = 32 * ii + 8 * gq + 4 * hh_e;        // column within the pass's 64
                     f32x4 x4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) x4[e] = u[4 * gq + e] * fin;
+                    for (int e = 0; e < 4; ++e) x4[e] = u[4 * gq + e] * fin[rb];
                     const u32x2 w2 = Mma<T>::pack4(x4);
-                    const int chunk = (dc >> 3) ^ (srow % C::CPR);
-                    *reinterpret_cast<u32x2*>(&stage[srow * D + 8 * chunk + (dc & 4)]) = w2;
+                    const int chunk = (dc >> 3) ^ ((col_e >> 1) & 7);
+                    *reinterpret_cast<u32x2*>(&stage[col_e * 64 + 8 * chunk + (dc & 4)]) = w2;
                 }
             }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        constexpr int NST = 64 * C::CPR / 64;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            u32x4 xs[4];
 #pragma unroll
-        for (int h = 0; h < NST; h += 8) {
-            u32x4 xs[8];
-#pragma unroll
-            for (int n8 = 0; n8 < 8; ++n8) {
-                const int slot = (h + n8) * 64 + lane_e;
-                const int r = slot / C::CPR;
-                const int c = slot % C::CPR;
-                xs[n8] = *reinterpret_cast<const u32x4*>(stage + r * D + 8 * (c ^ (r % C::CPR)));
+            for (int h = 0; h < 4; ++h) {
+                const int slot = h * 64 + lane_e;
+                const int r = slot >> 3, c = slot & 7;
+                xs[h] = *reinterpret_cast<const u32x4*>(stage + r * 64 + 8 * (c ^ ((r >> 1) & 7)));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int n8 = 0; n8 < 8; ++n8) {
-                const int slot = (h + n8) * 64 + lane_e;
-                const int r = slot / C::CPR;
-                const int c = slot % C::CPR;
+            for (int h = 0; h < 4; ++h) {
+                const int slot = h * 64 + lane_e;
+                const int r = 32 * rb + (slot >> 3), c = slot & 7;
                 if (cur.wrow0 + r < p.Lq)
                     __builtin_nontemporal_store(
-                        xs[n8],
-                        reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D + 8 * c));
+                        xs[h], reinterpret_cast<u32x4*>(cur.og + (size_t)(cur.wrow0 + r) * D +
+                                                        64 * hf + 8 * c));
             }
+            // (the next pass writes where this one has read: one wavefront's LDS accesses are
+            // served in the order it issued them)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
 }

@@ -148,7 +148,9 @@ def test_automatic_choice_of_the_prefill_kernel():
     T, W = flashd.VARIANT_TILE, flashd.VARIANT_TILE_256
     assert V(1, 32, 32, 16384, 16384, 128, BF, False) == W     # long, no mask
     assert V(4, 32, 32, 2048, 2048, 128, BF, False) == W       # 2048 keys are enough without a mask
-    assert V(4, 32, 32, 2048, 2048, 128, BF, True) == T        # the headline shape: short causal rows
+    assert V(4, 32, 32, 2048, 2048, 128, BF, True) == W        # the headline shape: two whole rounds of pairs
+    assert V(3, 32, 32, 2048, 2048, 128, BF, True) == T        # a round and a half
+    assert V(1, 32, 32, 2048, 2048, 128, BF, True) == T        # half the compute units
     assert V(1, 32, 32, 4096, 4096, 128, BF, True) == W        # rows see 2048 keys on average
     assert V(2, 32, 32, 3072, 3072, 128, BF, True) == W        # 1536 on average
     assert V(8, 32, 8, 512, 2048, 128, BF, True) == W          # short queries late in a long context

@@ -142,7 +142,7 @@ def test_wide_kernel_is_bitwise_reproducible_and_agrees_with_tile():
 def test_the_automatic_choice_takes_the_wide_kernel_where_it_says_so():
     """A shape flashd_auto_variant reports as TILE_256 (a workgroup per compute unit, 2048 keys,
     no mask): flashd_attn_fwd must return the 256-row kernel's bits, and they must agree with
-    the oracle; the headline shape (short causal rows) stays with the 128-row kernel."""
+    the oracle; short causal rows stay with the 128-row kernel."""
     w = synthetic.small("wide auto", 1, 64, 8, 1024, 2048, 128, "bf16", False, seed=9800)
     assert flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, flashd.BF16, False) == WIDE
     q, k, v, _ = synthetic.make_qkv(w)
