@@ -82,12 +82,13 @@ typedef enum {
     FLASHD_VARIANT_TILE_256 = 5        /* TILE on the kernel with 256 query rows per workgroup
                                           (one wavefront per SIMD, matrix and vector work
                                           interleaved by hand) where it can serve the call:
-                                          f16/bf16, d = 128, no splits, no state (rows past
-                                          the end of a head's last 256 are not stored); any other call runs as TILE.  Same
-                                          arithmetic; measured 7 to 18 % ahead of TILE on
-                                          long inputs and behind it on short causal
-                                          ones: the automatic choice takes it where it is
-                                          ahead (flashd_auto_variant)                      */
+                                          f16/bf16, d = 128, no splits, no state; any other
+                                          call runs as TILE.  Same
+                                          arithmetic; measured 6 to 16 % ahead of TILE on
+                                          long inputs, level with it at 2048 causal keys
+                                          and behind it on shorter ones: the automatic
+                                          choice takes it where it is ahead
+                                          (flashd_auto_variant)                            */
 } flashd_variant;
 
 /*

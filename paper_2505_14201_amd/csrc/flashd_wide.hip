@@ -26,8 +26,11 @@
 //   * The output accumulators, the Q fragments and the matrix operands live in fixed
 //     accumulation registers that only inline assembly touches (flashd_wide_regs.h).
 //
-// Blocks on which a mask applies or a row may still be empty (the first block, the diagonal
-// blocks of a causal mask, the tail), and any block under a negative scale, take the plain
+// A fused step also takes the blocks a mask applies to (a hidden key gets the score -inf where
+// the scores are scaled), a wavefront's last block (the scores it forms beside it are nobody's)
+// and a row tile's first (zero stands in for the rows' reference where their coefficients then
+// add up to a trusted amount).  Blocks some row of which may still be empty afterwards (a row
+// that sees no key of the first block), and any block under a negative scale, take the plain
 // steps (wide_first_general / wide_second).
 //
 // Serves f16/bf16, d = 128, unsplit calls without state in or out (wide_applies()); everything
