@@ -611,12 +611,10 @@ void wide_kernel(Problem p, TileSched sc) {
             wide_copy<D, false>(cur.kg, cur.jbase, p.Lk, dl, wave, lane, lds);
             wide_copy<D, true>(cur.vg, cur.jbase, p.Lk, dl, wave, lane, vs0);
         }
-        if (n > 1) {
-            wide_copy<D, false>(cur.kg, cur.jbase + kBC, p.Lk, dl, wave, lane, lds + kTile);
-            wide_copy<D, true>(cur.vg, cur.jbase + kBC, p.Lk, dl, wave, lane, vs0 + kTile);
-        }
-        if (n > 2)
-            wide_copy<D, false>(cur.kg, cur.jbase + 2 * kBC, p.Lk, dl, wave, lane, lds + 2 * kTile);
+        // (K of tile 1 is read in period 0 already; V of tile 1 and K of tile 2, which period 1
+        // reads, follow once the Q fragments are in their registers: the row tile starts when
+        // what it starts with has landed, and the copy path is the slowest part of that)
+        if (n > 1) wide_copy<D, false>(cur.kg, cur.jbase + kBC, p.Lk, dl, wave, lane, lds + kTile);
         int nvis[kWideRB];
         wide_zero_u();
         // (the lane index afresh, here and in the epilogue: what is formed from it then does
@@ -650,6 +648,9 @@ void wide_kernel(Problem p, TileSched sc) {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        if (n > 1) wide_copy<D, true>(cur.vg, cur.jbase + kBC, p.Lk, dl, wave, lane, vs0 + kTile);
+        if (n > 2)
+            wide_copy<D, false>(cur.kg, cur.jbase + 2 * kBC, p.Lk, dl, wave, lane, lds + 2 * kTile);
 
         f32x16 acc[2][kWideRB];          // scores of block b live in acc[b % 2]
         WidePacked pk[2];                // coefficients of block b (a fused step's) in pk[b % 2]
