@@ -543,7 +543,8 @@ __device__ __forceinline__ void wide_second(const uint16_t* vb, WideRegs<D>& g, 
     wide_pv<T, D>(vb, g, pk.g0, pk.g1);
 }
 
-// LDS: four K slots and four V slots, tile t in slot t % 4 of each.  In the period of tile t a
+// LDS: four K slots and four V slots, tile t in slot t % 4 of each, and a ninth slot that only
+// the Q rows pass through at the start of a row tile (with three of the others).  In the period of tile t a
 // wavefront forms the scores of the tile's second half and of the first half of tile t + 1, and
 // the output products of the second half of tile t - 1 and the first half of tile t: it reads
 // K(t), K(t + 1), V(t - 1) and V(t).  The copies of K(t + 3) and V(t + 2) are started in that
