@@ -48,7 +48,10 @@ def test_causal_prefill_config_and_its_shifted_values_twin():
     q, k, v, _ = synthetic.make_qkv(w)
     rows = rows_for(w, [(0, 0), (w.B - 1, w.Hq - 1), (1, 7)], 8192, seed=21)
     compare_rows(run_auto(q, k, v, w), q, k, v, w, rows, w.name)
-    for variant in (flashd.VARIANT_TILE_BLEND, flashd.VARIANT_ONLINE_SOFTMAX):
+    # both prefill kernels by name (whichever the automatic choice takes, bench.py times the
+    # other one beside it), the per-tile blend and the ablation
+    for variant in (flashd.VARIANT_TILE, flashd.VARIANT_TILE_256, flashd.VARIANT_TILE_BLEND,
+                    flashd.VARIANT_ONLINE_SOFTMAX):
         compare_rows(run_auto(q, k, v, w, variant), q, k, v, w, rows[::4],
                      f"{w.name} variant={variant}")
     # V + 1: outputs near 1, where the absolute bound of 2e-2 is a real constraint
@@ -61,6 +64,9 @@ def test_long_noncausal_prefill_config():
     q, k, v, _ = synthetic.make_qkv(w)
     rows = synthetic.sample_rows(w, 3072, seed=22)
     compare_rows(run_auto(q, k, v, w), q, k, v, w, rows, w.name)
+    for variant in (flashd.VARIANT_TILE, flashd.VARIANT_TILE_256):
+        compare_rows(run_auto(q, k, v, w, variant), q, k, v, w, rows[::4],
+                     f"{w.name} variant={variant}")
 
 
 def test_gqa_decode_config_in_full():
