@@ -188,7 +188,7 @@ def variant_legs(w, sets, steps, warmup):
     return out
 
 
-def prefill_leg(w, steps, warmup, nsets, profile, cpu=True, variants=True):
+def prefill_leg(w, steps, warmup, nsets, profile, cpu=True, variants=True, budget_flop=2.0e12):
     """One prefill configuration other than the headline one: flashd_attn_fwd timed with HIP
     events on the launch stream, its roofline, the other variants, parity and oracle speed."""
     from paper_2505_14201_amd import flashd
@@ -200,7 +200,7 @@ def prefill_leg(w, steps, warmup, nsets, profile, cpu=True, variants=True):
     _, ev = time_calls(step, steps, warmup, nsets)
     ms = ev / steps
     tf = w.flops() / (ms * 1e-3) / 1e12
-    traffic, src = profile_traffic(profile)
+    traffic, src = profile_traffic(profile) if profile else (None, None)
     leg = {"workload": w.name, "dtype": w.dtype, "steps": steps, "input_sets": nsets,
            "flop_per_step": w.flops(), "kernel_ms": round(ms, 4), "TFLOP/s": round(tf, 2),
            "roofline": {"bound": "mfma",
@@ -211,7 +211,7 @@ def prefill_leg(w, steps, warmup, nsets, profile, cpu=True, variants=True):
     if cpu:
         step(0)
         torch.cuda.synchronize()
-        leg["parity"], leg["cpu_baseline"] = oracle_leg(w, host, sets[0][3].cpu())
+        leg["parity"], leg["cpu_baseline"] = oracle_leg(w, host, sets[0][3].cpu(), budget_flop)
     if variants:
         leg.update(variant_legs(w, sets, steps, warmup))
     del sets
@@ -237,6 +237,9 @@ def main() -> int:
     ap.add_argument("--no-other-prefill", action="store_true",
                     help="skip the legs of the long non-causal, the stress and the single-head "
                          "configurations")
+    ap.add_argument("--no-long-causal", action="store_true",
+                    help="skip the leg of the causal mask at 16384 positions (not one of the "
+                         "five configurations)")
     ap.add_argument("--no-kv8", action="store_true", help="skip the fp8 K/V decode measurement")
     ap.add_argument("--no-skipv", action="store_true",
                     help="skip the peaked-score decode measurement (saturation skip on V)")
@@ -379,6 +382,15 @@ def main() -> int:
         out["prefill_c5"] = prefill_leg(synthetic.CONFIGS[4], args.steps, args.warmup, args.sets,
                                         PREFILL_PROFILE[4], cpu=not args.no_cpu,
                                         variants=not args.no_ablation)
+        # beside the five configurations: the causal mask at the length of the long workload
+        # (one sequence of 16384 positions), where a row tile's fixed costs weigh less than at
+        # the 2048 positions of the headline workload
+        if not args.no_long_causal:
+            wl = synthetic.small("x1_long_causal_prefill_bf16", 1, 32, 32, 16384, 16384, 128,
+                                 "bf16", True, seed=1602)
+            out["prefill_causal_16k"] = prefill_leg(wl, min(args.steps, 40), 4, 2, None,
+                                                    cpu=not args.no_cpu, variants=False,
+                                                    budget_flop=2.0e11)
         # the single fp32 head: launch-latency bound, reported in microseconds with its parity
         w1 = synthetic.CONFIGS[0]
         (q1, k1, v1), s1 = make_sets(w1, 1)
