@@ -150,6 +150,14 @@ def test_the_automatic_choice_takes_the_wide_kernel_where_it_says_so():
     wide = run_flashd(q, k, v, False, w.scale, WIDE, 1)
     assert torch.equal(auto.view(torch.int16), wide.view(torch.int16))
     sampled(auto, q, k, v, w, 1024, 37, "automatic choice, 256-row kernel")
+    # under a causal mask: short queries late in a longer context (rows see 1792 keys on average)
+    w = synthetic.small("wide auto causal", 8, 32, 8, 512, 2048, 128, "f16", True, seed=9802)
+    assert flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, flashd.F16, True) == WIDE
+    q, k, v, _ = synthetic.make_qkv(w)
+    auto = run_flashd(q, k, v, True, w.scale, use_ex=False)
+    wide = run_flashd(q, k, v, True, w.scale, WIDE, 1)
+    assert torch.equal(auto.view(torch.int16), wide.view(torch.int16))
+    sampled(auto, q, k, v, w, 1024, 38, "automatic choice under a causal mask, 256-row kernel")
     w = synthetic.small("wide auto no", 1, 8, 8, 1024, 1024, 128, "bf16", True, seed=9801)
     assert flashd.auto_variant(w.B, w.Hq, w.Hkv, w.Lq, w.Lk, w.d, flashd.BF16, True) == flashd.VARIANT_TILE
     q, k, v, _ = synthetic.make_qkv(w)
